@@ -1,0 +1,167 @@
+/*
+ * pyr.h - C ABI of the MI355X (gfx950) prefill layer step of PyramidInfer
+ * (arXiv 2405.12532, Algorithm 1 "One forward pass in PyramidInfer" and the
+ * prefill paragraph of Section 4.1).
+ *
+ * One layer step, for every sequence of a packed batch:
+ *   attention weights  ->  ensemble weights of the recent window  ->  TopP
+ *   ->  Gather of K, V (and of the hidden rows that feed the next layer).
+ *
+ * Conventions that hold for every function below
+ *   - returns PYR_OK (0) or a negative pyr_status; never throws;
+ *   - arguments are checked on the host before anything is launched; a
+ *     failed check launches nothing;
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *     host memory read during the call only; all buffers are caller-owned;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL is the
+ *     default stream); nothing synchronises the stream or the device and
+ *     nothing allocates or frees device memory;
+ *   - packed layouts, row-major, token-major, bfloat16 unless said otherwise:
+ *       q, out : [T, Hq, d]      k, v : [T, Hkv, d]      hidden : [T, D]
+ *     sequence b owns rows seq_offsets[b] .. seq_offsets[b+1]-1 (S_b rows);
+ *     query head h reads key/value head h / (Hq / Hkv);
+ *   - supported: d in {64, 128}, Hq % Hkv == 0, w >= 1, T < 2^31.
+ */
+#ifndef PYR_H
+#define PYR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define PYR_API __attribute__((visibility("default")))
+#else
+#define PYR_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pyr_status {
+    PYR_OK = 0,
+    PYR_ERR_NULL = -1,        /* a required pointer is NULL                               */
+    PYR_ERR_SHAPE = -2,       /* negative / inconsistent sizes                            */
+    PYR_ERR_UNSUPPORTED = -3, /* head_dim, head grouping or row size outside the set     */
+    PYR_ERR_KEEP_LEN = -4,    /* keep_len[b] outside [min(w, S_b), S_b]                   */
+    PYR_ERR_OFFSETS = -5,     /* seq_offsets not 0-based, not monotone, or != T at end    */
+    PYR_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or too small          */
+    PYR_ERR_LAUNCH = -7       /* the HIP runtime refused a launch (see hipGetLastError)   */
+} pyr_status;
+
+typedef struct pyr_shape {
+    int32_t n_seqs;       /* B                                   */
+    int32_t total_tokens; /* T = sum of S_b                      */
+    int32_t max_seqlen;   /* max S_b                             */
+    int32_t n_q_heads;    /* Hq                                  */
+    int32_t n_kv_heads;   /* Hkv                                 */
+    int32_t head_dim;     /* d                                   */
+} pyr_shape;
+
+/* Text for a status code (static storage, never NULL). */
+PYR_API const char* pyr_strerror(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+PYR_API int pyr_version(void);
+
+/*
+ * Host only.  Bytes of device workspace pyr_prefill_layer needs for this
+ * shape and window (row statistics of the softmax for the score pass and the
+ * tile map of ragged batches).  Align the buffer to 256 bytes.
+ */
+PYR_API int pyr_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out);
+
+/*
+ * Host only.  Retention count for the next layer (Algorithm 1: the ratio p is
+ * reduced layer by layer, and a layer whose length is at or below the minimum
+ * PvC length N_l is left alone):
+ *   k = max(floor((num*S + den/2)/den), floor_len, min(w, S)), capped at S.
+ * Errors: PYR_ERR_NULL, PYR_ERR_SHAPE (S < 0, w < 1, den <= 0, num < 0, num > den).
+ */
+PYR_API int pyr_schedule_next(int32_t S, int32_t w, int32_t num, int32_t den, int32_t floor_len,
+                      int32_t* keep_len_out);
+
+/*
+ * Step 1 - attention weights applied to V (Algorithm 1, "compute attention
+ * weights of KV"): causal softmax attention inside each sequence,
+ *   out[i,h,:] = sum_{j<=i} softmax_j(scale * q[i,h,:].k[j,h/g,:]) v[j,h/g,:].
+ * bf16 MFMA products, fp32 accumulation and fp32 online softmax.
+ *   q, k, v            dev, in
+ *   seq_offsets_dev    dev int32 [B+1];  seq_offsets_host  host copy of the same
+ *   softmax_scale      <= 0 selects 1/sqrt(d)
+ *   out                dev bf16 [T,Hq,d], written
+ *   lse                dev fp32 [T,Hq], written: log2 of the softmax denominator of
+ *                      every row, in the scaled base-2 domain,
+ *                      lse[i,h] = log2(sum_j 2^(scale*log2(e)*s_ij)); may be NULL
+ *   tile_map           dev int32 [B+1] scratch, written (prefix sums of query
+ *                      tiles per sequence); part of the workspace
+ */
+PYR_API int pyr_attention(const void* q, const void* k, const void* v,
+                  const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                  const pyr_shape* shape, float softmax_scale,
+                  void* out, float* lse, int32_t* tile_map, void* stream);
+
+/*
+ * Step 2 - ensemble attention weights (Algorithm 1, A_e = weighted_avg(A[-L:, :-L]);
+ * Section 3.2.1): for every key position t of every sequence
+ *   scores[t] = 1/(Hq*L') * sum_h sum_{i=S-L'}^{S-1} A_h[i,t],   L' = min(w, S),
+ * uniform weights, all S columns written (the last L' too), fixed summation
+ * order (bit-reproducible).  Needs `lse` from pyr_attention.
+ *   scores             dev fp32 [T], written
+ */
+PYR_API int pyr_score(const void* q, const void* k, const float* lse,
+              const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+              const pyr_shape* shape, int32_t w, float softmax_scale,
+              float* scores, void* stream);
+
+/*
+ * Step 3 - TopP (Algorithm 1, TopP(A_e, p) with a count: Section 3.1.1 calls p
+ * a retention ratio): per sequence the keep_len[b]-L' context positions
+ * (0 .. S_b-L'-1) with the largest score, ties to the lower position, plus the
+ * last L' positions; ascending.  Exact on the fp32 values given.
+ *   scores             dev fp32 [T], in, all values >= 0 and not NaN
+ *   keep_len_dev       dev int32 [B];  keep_len_host  host copy, min(w,S_b) <= k_b <= S_b
+ *   kept_idx           dev int32 [sum k_b], written: global packed row numbers
+ *   out_offsets_dev    dev int32 [B+1], written: prefix sums of keep_len
+ */
+PYR_API int pyr_select(const float* scores,
+               const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+               const int32_t* keep_len_dev, const int32_t* keep_len_host,
+               int32_t n_seqs, int32_t w,
+               int32_t* kept_idx, int32_t* out_offsets_dev, void* stream);
+
+/*
+ * Steps 4/5 - Gather (Algorithm 1, PvC <- Gather(KV, index); Figure 2(c): the
+ * next layer only computes the kept tokens): dst[j,:] = src[kept_idx[j],:]
+ * for j < n_kept, byte-exact.
+ *   src, dst           dev, rows of row_bytes bytes (a multiple of 16, both
+ *                      16-byte aligned), dst must not overlap src
+ *   kept_idx           dev int32 [n_kept], every value a valid row of src
+ *   n_kept == 0 is a no-op.
+ */
+PYR_API int pyr_compact(const void* src, size_t row_bytes, const int32_t* kept_idx, int64_t n_kept,
+                void* dst, void* stream);
+
+/* Same as two pyr_compact calls with one index list, in a single launch (K and V). */
+PYR_API int pyr_compact2(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
+                 const int32_t* kept_idx, int64_t n_kept, void* stream);
+
+/*
+ * The whole layer step (Algorithm 1, body of the loop, prefill phase):
+ * pyr_attention -> pyr_score -> pyr_select -> pyr_compact2 on one stream.
+ *   scores             dev fp32 [T], written (required: the selection reads it)
+ *   k_out, v_out       dev bf16 [sum k_b, Hkv, d]; both NULL skips the gather
+ *   workspace          dev, >= pyr_workspace_bytes(), 256-byte aligned
+ */
+PYR_API int pyr_prefill_layer(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PYR_H */

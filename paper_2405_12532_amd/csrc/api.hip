@@ -1,0 +1,239 @@
+// C ABI of libpyr: argument checks on the host, then the launchers.  See include/pyr.h for
+// the contract of every entry point (Algorithm 1 and Section 4.1 of the paper).
+#include <math.h>
+
+#include "pyr_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct BatchInfo {
+    int32_t uniform_len;    // common length if all sequences have one (> 0), else 0
+    int32_t max_len;
+    int64_t q_tiles;        // sum over sequences of ceil(S_b / kAttnBlockRows)
+};
+
+int check_shape(const pyr_shape* s) {
+    if (s == nullptr) return PYR_ERR_NULL;
+    if (s->n_seqs < 0 || s->total_tokens < 0 || s->max_seqlen < 0 || s->n_q_heads < 1 || s->n_kv_heads < 1)
+        return PYR_ERR_SHAPE;
+    if (s->max_seqlen > s->total_tokens) return PYR_ERR_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 128) return PYR_ERR_UNSUPPORTED;
+    if (s->n_q_heads % s->n_kv_heads != 0) return PYR_ERR_UNSUPPORTED;
+    // the kernels index elements of q with 64-bit offsets, but row numbers stay 32-bit
+    if ((int64_t)s->total_tokens * s->n_q_heads >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
+    return PYR_OK;
+}
+
+int check_offsets(const int32_t* off, int32_t n_seqs, int32_t total, int32_t max_len_claimed, BatchInfo* info) {
+    if (off == nullptr) return PYR_ERR_NULL;
+    if (off[0] != 0) return PYR_ERR_OFFSETS;
+    int32_t max_len = 0, first = n_seqs > 0 ? off[1] - off[0] : 0;
+    bool uniform = n_seqs > 0;
+    int64_t tiles = 0;
+    for (int32_t b = 0; b < n_seqs; ++b) {
+        if (off[b + 1] < off[b]) return PYR_ERR_OFFSETS;
+        const int32_t len = off[b + 1] - off[b];
+        if (len > max_len) max_len = len;
+        if (len != first) uniform = false;
+        tiles += (len + pyr::kAttnBlockRows - 1) / pyr::kAttnBlockRows;
+    }
+    if (off[n_seqs] != total) return PYR_ERR_OFFSETS;
+    if (max_len_claimed >= 0 && max_len > max_len_claimed) return PYR_ERR_SHAPE;
+    if (info != nullptr) {
+        info->uniform_len = (uniform && first > 0) ? first : 0;
+        info->max_len = max_len;
+        info->q_tiles = tiles;
+    }
+    return PYR_OK;
+}
+
+int check_keep_len(const int32_t* keep, const int32_t* off, int32_t n_seqs, int32_t w, int64_t* total_kept) {
+    if (keep == nullptr) return PYR_ERR_NULL;
+    int64_t sum = 0;
+    for (int32_t b = 0; b < n_seqs; ++b) {
+        const int32_t len = off[b + 1] - off[b];
+        const int32_t lo = w < len ? w : len;
+        if (keep[b] < lo || keep[b] > len) return PYR_ERR_KEEP_LEN;
+        sum += keep[b];
+    }
+    if (total_kept != nullptr) *total_kept = sum;
+    return PYR_OK;
+}
+
+float scale_log2(float softmax_scale, int head_dim) {
+    const float s = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+    return s * pyr::kLog2e;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* pyr_strerror(int status) {
+    switch (status) {
+        case PYR_OK: return "ok";
+        case PYR_ERR_NULL: return "a required pointer is NULL";
+        case PYR_ERR_SHAPE: return "negative or inconsistent sizes";
+        case PYR_ERR_UNSUPPORTED: return "unsupported head_dim, head grouping, row size or alignment";
+        case PYR_ERR_KEEP_LEN: return "keep_len outside [min(w, S), S]";
+        case PYR_ERR_OFFSETS: return "seq_offsets not 0-based, not monotone or not ending at total_tokens";
+        case PYR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PYR_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown pyr status";
+    }
+}
+
+int pyr_version(void) { return 100; }
+
+int pyr_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out) {
+    if (bytes_out == nullptr) return PYR_ERR_NULL;
+    const int rc = check_shape(shape);
+    if (rc != PYR_OK) return rc;
+    if (w < 1) return PYR_ERR_SHAPE;
+    *bytes_out = align_up((size_t)shape->total_tokens * shape->n_q_heads * sizeof(float)) +
+                 align_up(((size_t)shape->n_seqs + 1) * sizeof(int32_t));
+    return PYR_OK;
+}
+
+int pyr_schedule_next(int32_t S, int32_t w, int32_t num, int32_t den, int32_t floor_len, int32_t* keep_len_out) {
+    if (keep_len_out == nullptr) return PYR_ERR_NULL;
+    if (S < 0 || w < 1 || den <= 0 || num < 0 || num > den || floor_len < 0) return PYR_ERR_SHAPE;
+    int64_t k = ((int64_t)num * S + den / 2) / den;
+    const int64_t recent = w < S ? w : S;
+    if (k < floor_len) k = floor_len;
+    if (k < recent) k = recent;
+    if (k > S) k = S;
+    *keep_len_out = (int32_t)k;
+    return PYR_OK;
+}
+
+int pyr_attention(const void* q, const void* k, const void* v,
+                  const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                  const pyr_shape* shape, float softmax_scale,
+                  void* out, float* lse, int32_t* tile_map, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != PYR_OK) return rc;
+    if (!q || !k || !v || !out || !seq_offsets_dev || !seq_offsets_host) return PYR_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return PYR_ERR_UNSUPPORTED;
+    BatchInfo info;
+    rc = check_offsets(seq_offsets_host, shape->n_seqs, shape->total_tokens, shape->max_seqlen, &info);
+    if (rc != PYR_OK) return rc;
+    if (info.uniform_len == 0 && info.q_tiles > 0 && tile_map == nullptr) return PYR_ERR_WORKSPACE;
+    if (info.q_tiles * shape->n_q_heads >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
+    return pyr::launch_attention(q, k, v, seq_offsets_dev, *shape, info.uniform_len, info.q_tiles,
+                                 scale_log2(softmax_scale, shape->head_dim), out, lse, tile_map,
+                                 (hipStream_t)stream);
+}
+
+int pyr_score(const void* q, const void* k, const float* lse,
+              const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+              const pyr_shape* shape, int32_t w, float softmax_scale,
+              float* scores, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != PYR_OK) return rc;
+    if (w < 1) return PYR_ERR_SHAPE;
+    if (!q || !k || !lse || !scores || !seq_offsets_dev || !seq_offsets_host) return PYR_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k)) return PYR_ERR_UNSUPPORTED;
+    BatchInfo info;
+    rc = check_offsets(seq_offsets_host, shape->n_seqs, shape->total_tokens, shape->max_seqlen, &info);
+    if (rc != PYR_OK) return rc;
+    pyr_shape s = *shape;
+    s.max_seqlen = info.max_len;
+    return pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, scale_log2(softmax_scale, shape->head_dim),
+                             scores, (hipStream_t)stream);
+}
+
+int pyr_select(const float* scores,
+               const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+               const int32_t* keep_len_dev, const int32_t* keep_len_host,
+               int32_t n_seqs, int32_t w,
+               int32_t* kept_idx, int32_t* out_offsets_dev, void* stream) {
+    if (n_seqs < 0 || w < 1) return PYR_ERR_SHAPE;
+    if (!scores || !seq_offsets_dev || !seq_offsets_host || !keep_len_dev || !keep_len_host || !kept_idx ||
+        !out_offsets_dev)
+        return PYR_ERR_NULL;
+    BatchInfo info;
+    int rc = check_offsets(seq_offsets_host, n_seqs, seq_offsets_host[n_seqs < 0 ? 0 : n_seqs], -1, &info);
+    if (rc != PYR_OK) return rc;
+    rc = check_keep_len(keep_len_host, seq_offsets_host, n_seqs, w, nullptr);
+    if (rc != PYR_OK) return rc;
+    return pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, n_seqs, info.max_len, w, kept_idx,
+                              out_offsets_dev, (hipStream_t)stream);
+}
+
+int pyr_compact2(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
+                 const int32_t* kept_idx, int64_t n_kept, void* stream) {
+    if (n_kept < 0) return PYR_ERR_SHAPE;
+    if (n_kept == 0) return PYR_OK;
+    if (!src0 || !dst0 || !src1 || !dst1 || !kept_idx) return PYR_ERR_NULL;
+    if (row_bytes == 0 || row_bytes % 16 != 0 || row_bytes / 16 > 0x7fffffff) return PYR_ERR_UNSUPPORTED;
+    if (!aligned16(src0) || !aligned16(dst0) || !aligned16(src1) || !aligned16(dst1)) return PYR_ERR_UNSUPPORTED;
+    return pyr::launch_gather(src0, dst0, src1, dst1, row_bytes, kept_idx, n_kept, (hipStream_t)stream);
+}
+
+int pyr_compact(const void* src, size_t row_bytes, const int32_t* kept_idx, int64_t n_kept,
+                void* dst, void* stream) {
+    if (n_kept < 0) return PYR_ERR_SHAPE;
+    if (n_kept == 0) return PYR_OK;
+    if (!src || !dst || !kept_idx) return PYR_ERR_NULL;
+    if (row_bytes == 0 || row_bytes % 16 != 0 || row_bytes / 16 > 0x7fffffff) return PYR_ERR_UNSUPPORTED;
+    if (!aligned16(src) || !aligned16(dst)) return PYR_ERR_UNSUPPORTED;
+    return pyr::launch_gather(src, dst, nullptr, nullptr, row_bytes, kept_idx, n_kept, (hipStream_t)stream);
+}
+
+int pyr_prefill_layer(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != PYR_OK) return rc;
+    if (w < 1) return PYR_ERR_SHAPE;
+    if (!q || !k || !v || !out || !scores || !kept_idx || !out_offsets_dev || !seq_offsets_dev ||
+        !seq_offsets_host || !keep_len_dev || !keep_len_host)
+        return PYR_ERR_NULL;
+    if ((k_out == nullptr) != (v_out == nullptr)) return PYR_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(k_out) || !aligned16(v_out))
+        return PYR_ERR_UNSUPPORTED;
+    BatchInfo info;
+    rc = check_offsets(seq_offsets_host, shape->n_seqs, shape->total_tokens, shape->max_seqlen, &info);
+    if (rc != PYR_OK) return rc;
+    int64_t total_kept = 0;
+    rc = check_keep_len(keep_len_host, seq_offsets_host, shape->n_seqs, w, &total_kept);
+    if (rc != PYR_OK) return rc;
+    size_t need = 0;
+    rc = pyr_workspace_bytes(shape, w, &need);
+    if (rc != PYR_OK) return rc;
+    if (workspace == nullptr || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return PYR_ERR_WORKSPACE;
+    if (info.q_tiles * shape->n_q_heads >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
+
+    float* lse = (float*)workspace;
+    int32_t* tile_map =
+        (int32_t*)((char*)workspace + align_up((size_t)shape->total_tokens * shape->n_q_heads * sizeof(float)));
+    hipStream_t st = (hipStream_t)stream;
+    const float c = scale_log2(softmax_scale, shape->head_dim);
+    pyr_shape s = *shape;
+    s.max_seqlen = info.max_len;
+
+    rc = pyr::launch_attention(q, k, v, seq_offsets_dev, s, info.uniform_len, info.q_tiles, c, out, lse, tile_map, st);
+    if (rc != PYR_OK) return rc;
+    rc = pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, c, scores, st);
+    if (rc != PYR_OK) return rc;
+    rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
+                            out_offsets_dev, st);
+    if (rc != PYR_OK) return rc;
+    if (k_out != nullptr && total_kept > 0) {
+        const size_t row_bytes = (size_t)shape->n_kv_heads * shape->head_dim * 2;
+        rc = pyr::launch_gather(k, k_out, v, v_out, row_bytes, kept_idx, total_kept, st);
+    }
+    return rc;
+}
+
+}  // extern "C"

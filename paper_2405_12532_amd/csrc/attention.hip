@@ -1,0 +1,366 @@
+// Causal softmax attention over packed, ragged sequences (Algorithm 1, "compute attention
+// weights of KV", applied to V), flash style: the S x S weight matrix never exists.
+//
+// Work split.  One workgroup owns kBM = 256 consecutive query positions of one (sequence,
+// query head); its wavefronts each own 32-row blocks.  With two blocks per wavefront, wave
+// i takes blocks i and 7-i, so every wavefront sees the same number of causal key tiles.
+// Keys/values stream through LDS in tiles of 64 positions, double buffered, loaded with
+// 16-byte accesses one tile ahead of the arithmetic.
+//
+// MFMA mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts).  The kernel computes the
+// TRANSPOSED logits  S^T = K Q^T  (keys x queries): in the accumulator layout a lane then
+// holds 16 keys of ONE query column, so the softmax row statistics are per-lane scalars (one
+// exchange with lane^32 completes them) and rescaling the output is a per-lane multiply.
+// The output is accumulated transposed too,  O^T += V^T P^T,  whose B operand P^T is exactly
+// what the lane already holds once the K rows of a 32-key sub-tile are fed in the order
+// "bits 2 and 3 of the row number swapped".  V is transposed on its way into LDS.
+//
+// Numerics: bf16 products, fp32 accumulation, fp32 online softmax in base 2 with the scale
+// folded into one FMA per logit; probabilities are rounded to bf16 for the PV product while
+// the softmax denominator is summed from the unrounded fp32 values.
+#include "pyr_internal.h"
+
+namespace pyr {
+namespace {
+
+constexpr int kBN = 64;                    // key positions per LDS tile
+
+template <int D>
+struct Tile {
+    static constexpr int kKStride = D + 8;         // bf16 elements per K row (+16 B: conflict-free b128 reads)
+    static constexpr int kVStride = kBN + 8;       // bf16 elements per V^T row
+    static constexpr int kKElems = kBN * kKStride;
+    static constexpr int kVElems = D * kVStride;
+    static constexpr int kStageElems = kKElems + kVElems;
+    static constexpr size_t kLdsBytes = 2 * (size_t)kStageElems * sizeof(uint16_t);
+};
+
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+
+// prefix sums of the number of query tiles per sequence (ragged batches only)
+__global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
+                                                        int32_t block_rows, int32_t* __restrict__ tile_map) {
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int chunk = (n_seqs + 1023) / 1024;
+    const int lo = min(tid * chunk, n_seqs), hi = min(lo + chunk, n_seqs);
+    int sum = 0;
+    for (int b = lo; b < hi; ++b) sum += (seq_offsets[b + 1] - seq_offsets[b] + block_rows - 1) / block_rows;
+    part[tid] = sum;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {
+        const int add = tid >= d ? part[tid - d] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int run = part[tid] - sum;
+    for (int b = lo; b < hi; ++b) {
+        tile_map[b] = run;
+        run += (seq_offsets[b + 1] - seq_offsets[b] + block_rows - 1) / block_rows;
+    }
+    if (tid == 1023) tile_map[n_seqs] = part[1023];
+}
+
+template <int D, int QB, int NW>
+__global__ __launch_bounds__(NW * 64) void attention_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ tile_map,
+    int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds, float c,
+    uint16_t* __restrict__ out, float* __restrict__ lse) {
+    using T = Tile<D>;
+    constexpr int kNT = NW * 64;
+    constexpr int kBM = NW * QB * 32;
+    constexpr int kNSub = NW * QB;
+    constexpr int kKSteps = D / 16;               // MFMA k-steps over the head dimension
+    constexpr int kDTiles = D / 32;               // 32-row tiles of O^T
+    constexpr int kChunks = D / 8;                // 16-byte chunks per K/V row
+    constexpr int kItems = kChunks * (kBN / 4);   // (chunk, 4-key group) load items per matrix and tile
+    constexpr int kItemsPerThread = (kItems + kNT - 1) / kNT;
+    static_assert(kBM == kAttnBlockRows, "the host tile map assumes this block height");
+
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31;                     // row (A operand) / column (B, C) inside a 32-wide tile
+    const int gl = lane >> 5;                     // which half of the k-slots / accumulator rows
+
+    // ---- which (sequence, head, query tile).  Consecutive workgroup ids go to different XCDs
+    // (round robin), so the id is first split into (xcd, slot) and all query tiles and all
+    // query heads of one KV head are given to one XCD, heavy (late) tiles first: concurrently
+    // running workgroups of an XCD then read the same K/V rows through its L2.
+    const int group = n_q_heads / n_kv_heads;
+    const int xcd = blockIdx.x % xcds;
+    const long long slot = blockIdx.x / xcds;
+    const long long per_tile = (long long)(n_kv_heads / xcds) * group;
+    int b, n_tiles_b, tiles_before;
+    if (uniform_len > 0) {
+        n_tiles_b = (uniform_len + kBM - 1) / kBM;
+        b = (int)(slot / (per_tile * n_tiles_b));
+        tiles_before = b * n_tiles_b;
+    } else {
+        int lo = 0, hi = n_seqs;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (per_tile * tile_map[mid] <= slot) lo = mid; else hi = mid;
+        }
+        b = lo;
+        tiles_before = tile_map[b];
+        n_tiles_b = tile_map[b + 1] - tiles_before;
+    }
+    const long long rem = slot - per_tile * tiles_before;
+    const int kv_local = (int)(rem / ((long long)n_tiles_b * group));
+    const int rem2 = (int)(rem % ((long long)n_tiles_b * group));
+    const int q_tile = n_tiles_b - 1 - rem2 / group;
+    const int kvh = kv_local * xcds + xcd;
+    const int h = kvh * group + rem2 % group;
+
+    const int row0 = seq_offsets[b];
+    const int S = seq_offsets[b + 1] - row0;
+    const int q_base = q_tile * kBM;
+    const int n_kv_tiles = (min(S, q_base + kBM) + kBN - 1) / kBN;
+
+    int qlo[QB];
+    if (QB == 2) { qlo[0] = q_base + 32 * wave; qlo[QB - 1] = q_base + 32 * (kNSub - 1 - wave); }
+    else         { qlo[0] = q_base + 32 * wave; }
+
+    // ---- query fragments stay in registers for the whole sweep (B operand of S^T = K Q^T)
+    bf16x8 qf[QB][kKSteps];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int row = min(qlo[qb] + li, S - 1);
+        const uint16_t* src = q + ((size_t)(row0 + row) * n_q_heads + h) * D + 8 * gl;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
+    }
+
+    f32x16 oacc[QB][kDTiles];
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[qb][dt][r] = 0.f;
+    }
+
+    // ---- K/V tile movement: global -> registers (one tile ahead) -> LDS
+    u32x4 kreg[kItemsPerThread][4], vreg[kItemsPerThread][4];
+    const uint16_t* kbase_ptr = k + ((size_t)row0 * n_kv_heads + kvh) * D;
+    const uint16_t* vbase_ptr = v + ((size_t)row0 * n_kv_heads + kvh) * D;
+    const size_t tok_stride = (size_t)n_kv_heads * D;
+
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int it = 0; it < kItemsPerThread; ++it) {
+            const int item = tid + it * kNT;
+            if (kItems % kNT == 0 || item < kItems) {
+                const int dc = item % kChunks, kq = item / kChunks;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = min(t * kBN + 4 * kq + e, S - 1);
+                    kreg[it][e] = *(const u32x4*)(kbase_ptr + key * tok_stride + dc * 8);
+                    vreg[it][e] = *(const u32x4*)(vbase_ptr + key * tok_stride + dc * 8);
+                }
+            }
+        }
+    };
+    auto store_tile = [&](int stage) {
+        uint16_t* Ks = smem + stage * T::kStageElems;
+        uint16_t* Vt = Ks + T::kKElems;
+#pragma unroll
+        for (int it = 0; it < kItemsPerThread; ++it) {
+            const int item = tid + it * kNT;
+            if (kItems % kNT == 0 || item < kItems) {
+                const int dc = item % kChunks, kq = item / kChunks;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    *(u32x4*)(Ks + (4 * kq + e) * T::kKStride + dc * 8) = kreg[it][e];
+                // 4 keys x 8 dims  ->  8 rows (dims) x 4 keys
+#pragma unroll
+                for (int dd = 0; dd < 8; ++dd) {
+                    const int wsel = dd >> 1;
+                    uint32_t e0 = vreg[it][0][wsel], e1 = vreg[it][1][wsel], e2 = vreg[it][2][wsel], e3 = vreg[it][3][wsel];
+                    u32x2 pk;
+                    if (dd & 1) { pk[0] = (e0 >> 16) | (e1 & 0xffff0000u); pk[1] = (e2 >> 16) | (e3 & 0xffff0000u); }
+                    else        { pk[0] = (e0 & 0xffffu) | (e1 << 16);     pk[1] = (e2 & 0xffffu) | (e3 << 16); }
+                    *(u32x2*)(Vt + (dc * 8 + dd) * T::kVStride + 4 * kq) = pk;
+                }
+            }
+        }
+    };
+
+    // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
+    const int krow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
+
+    // softmax + PV for the q-blocks [QB0, QB) of this wavefront on the tile in `stage`
+    auto compute_tile = [&](int t, int stage, auto first_active) {
+        constexpr int kFirst = decltype(first_active)::value;
+        const uint16_t* Ks = smem + stage * T::kStageElems;
+        const uint16_t* Vt = Ks + T::kKElems;
+        const int key0 = t * kBN;
+
+        f32x16 sacc[QB][2];
+#pragma unroll
+        for (int qb = kFirst; qb < QB; ++qb)
+#pragma unroll
+            for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[qb][sk][r] = 0.f;
+
+#pragma unroll
+        for (int sk = 0; sk < 2; ++sk) {
+            const uint16_t* krow_ptr = Ks + (32 * sk + krow) * T::kKStride + 8 * gl;
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) {
+                const bf16x8 kf = *(const bf16x8*)(krow_ptr + 16 * ks);
+#pragma unroll
+                for (int qb = kFirst; qb < QB; ++qb)
+                    sacc[qb][sk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][sk], 0, 0, 0);
+            }
+        }
+
+        bf16x8 pf[QB][4];
+#pragma unroll
+        for (int qb = kFirst; qb < QB; ++qb) {
+            const int qrow = qlo[qb] + li;
+            const bool need_mask = (key0 + kBN - 1 > qlo[qb]) || (key0 + kBN > S);   // wave-uniform
+            if (need_mask) {
+#pragma unroll
+                for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + 32 * sk + 16 * (r >> 3) + 8 * gl + (r & 7);
+                        if (key > qrow || key >= S) sacc[qb][sk][r] = -INFINITY;
+                    }
+            }
+            float mx = sacc[qb][0][0];
+#pragma unroll
+            for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[qb][sk][r]);
+            mx = fmaxf(mx, other_half(mx));
+            const float m_new = fmaxf(m_run[qb], mx);
+            if (__ballot(m_new != m_run[qb]) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
+                l_run[qb] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[qb][dt][r] *= alpha;
+                m_run[qb] = m_new;
+            }
+            const float mc = m_new * c;
+            float lsum = 0.f;
+#pragma unroll
+            for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    bf16x8 pk;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][sk][8 * a + e], c, -mc));
+                        lsum += p;
+                        pk[e] = (__bf16)p;
+                    }
+                    pf[qb][2 * sk + a] = pk;
+                }
+            l_run[qb] += lsum;
+        }
+
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt) {
+            const uint16_t* vrow_ptr = Vt + (32 * dt + li) * T::kVStride + 8 * gl;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 vf = *(const bf16x8*)(vrow_ptr + 16 * ks);
+#pragma unroll
+                for (int qb = kFirst; qb < QB; ++qb)
+                    oacc[qb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], oacc[qb][dt], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main sweep over the key tiles
+    load_tile(0);
+    store_tile(0);
+    for (int t = 0; t < n_kv_tiles; ++t) {
+        __syncthreads();
+        const bool more = t + 1 < n_kv_tiles;
+        if (more) load_tile(t + 1);
+        const int key0 = t * kBN;
+        // a q-block takes part while some key of the tile is visible to its last row
+        if (QB == 2 && key0 <= qlo[0] + 31) {
+            compute_tile(t, t & 1, std::integral_constant<int, 0>{});
+        } else if (key0 <= qlo[QB - 1] + 31) {
+            compute_tile(t, t & 1, std::integral_constant<int, QB - 1>{});
+        }
+        if (more) store_tile((t + 1) & 1);
+    }
+
+    // ---- epilogue: normalise, round to bf16, store; log2 of the denominator for the score pass
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float ltot = l_run[qb] + other_half(l_run[qb]);
+        const float inv = 1.0f / ltot;
+        const int qrow = qlo[qb] + li;
+        if (qrow < S) {
+            uint16_t* dst = out + ((size_t)(row0 + qrow) * n_q_heads + h) * D + 4 * gl;
+#pragma unroll
+            for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[qb][dt][4 * a + e] * inv);
+                    *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
+                }
+            if (lse != nullptr && gl == 0)
+                lse[(size_t)(row0 + qrow) * n_q_heads + h] = m_run[qb] * c + __builtin_amdgcn_logf(ltot);
+        }
+    }
+}
+
+template <int D>
+int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
+                       const pyr_shape& s, int32_t uniform_len, int64_t total_q_tiles, float c,
+                       void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
+    constexpr int QB = 2, NW = 4;
+    auto kern = attention_kernel<D, QB, NW>;
+    static bool attr_done = false;   // benign race: the attribute call is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)Tile<D>::kLdsBytes) != hipSuccess)
+            return PYR_ERR_LAUNCH;
+        attr_done = true;
+    }
+    if (uniform_len == 0) {
+        hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs,
+                           (int32_t)kAttnBlockRows, tile_map);
+        if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
+    }
+    const int64_t n_blocks = total_q_tiles * s.n_q_heads;
+    if (n_blocks == 0) return PYR_OK;
+    const int xcds = (s.n_kv_heads % 8 == 0) ? 8 : 1;
+    hipLaunchKernelGGL(kern, dim3((unsigned)n_blocks), dim3(NW * 64), Tile<D>::kLdsBytes, stream,
+                       (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, seq_offsets_dev,
+                       (const int32_t*)tile_map, s.n_seqs, s.n_q_heads, s.n_kv_heads, uniform_len, xcds, c,
+                       (uint16_t*)out, lse);
+    return check_launch();
+}
+
+}  // namespace
+
+int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
+                     const pyr_shape& shape, int32_t uniform_len, int64_t total_q_tiles, float scale_log2,
+                     void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
+    if (shape.head_dim == 128)
+        return launch_attention_d<128>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
+                                       out, lse, tile_map, stream);
+    return launch_attention_d<64>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
+                                  out, lse, tile_map, stream);
+}
+
+}  // namespace pyr

@@ -1,0 +1,61 @@
+// Row gather: dst[j, :] = src[kept_idx[j], :]   (Algorithm 1, Gather(KV, index); the same
+// kernel compacts the hidden rows that enter the next layer).
+//
+// Pure data movement, bound by HBM bandwidth: 2 * n_kept * row_bytes bytes move per source.
+// One wavefront owns one output row at a time; its 64 lanes move 16 bytes each per access,
+// so a row is read and written in fully coalesced 1 KiB pieces, and up to kUnroll loads per
+// lane are issued before the first store to keep enough bytes in flight per compute unit.
+#include "pyr_internal.h"
+
+namespace pyr {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;
+constexpr int kUnroll = 8;
+
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(
+    const u32x4* __restrict__ src0, u32x4* __restrict__ dst0,
+    const u32x4* __restrict__ src1, u32x4* __restrict__ dst1,
+    const int32_t* __restrict__ kept_idx, int64_t n_rows, int32_t chunks_per_row) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const u32x4* __restrict__ src = blockIdx.y == 0 ? src0 : src1;
+    u32x4* __restrict__ dst = blockIdx.y == 0 ? dst0 : dst1;
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    for (int64_t j = (int64_t)blockIdx.x * kWavesPerBlock + wave; j < n_rows; j += wave_stride) {
+        const int64_t from = (int64_t)kept_idx[j] * chunks_per_row;
+        const int64_t to = j * chunks_per_row;
+        for (int c0 = 0; c0 < chunks_per_row; c0 += 64 * kUnroll) {
+            u32x4 buf[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < chunks_per_row) buf[u] = __builtin_nontemporal_load(src + from + c);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < chunks_per_row) __builtin_nontemporal_store(buf[u], dst + to + c);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int launch_gather(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
+                  const int32_t* kept_idx, int64_t n_kept, hipStream_t stream) {
+    if (n_kept == 0) return PYR_OK;
+    const int32_t chunks = (int32_t)(row_bytes / 16);
+    int64_t blocks = (n_kept + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t cap = 256 * 64;   // plenty of workgroups per compute unit; the rest is the stride loop
+    if (blocks > cap) blocks = cap;
+    dim3 grid((unsigned)blocks, src1 != nullptr ? 2 : 1, 1);
+    hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(kThreads), 0, stream,
+                       (const u32x4*)src0, (u32x4*)dst0, (const u32x4*)src1, (u32x4*)dst1,
+                       kept_idx, n_kept, chunks);
+    return check_launch();
+}
+
+}  // namespace pyr

@@ -1,0 +1,40 @@
+// Internal declarations shared by the translation units of libpyr (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pyr.h"
+
+namespace pyr {
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Rows of query positions one attention workgroup owns (the tile map counts these).
+constexpr int kAttnBlockRows = 256;
+
+// Every launcher returns PYR_OK or PYR_ERR_LAUNCH; arguments are already validated.
+int launch_gather(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
+                  const int32_t* kept_idx, int64_t n_kept, hipStream_t stream);
+
+int launch_select(const float* scores, const int32_t* seq_offsets_dev, const int32_t* keep_len_dev,
+                  int32_t n_seqs, int32_t max_seqlen, int32_t w, int32_t* kept_idx, int32_t* out_offsets_dev,
+                  hipStream_t stream);
+
+int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
+                     const pyr_shape& shape, int32_t uniform_len, int64_t total_q_tiles, float scale_log2,
+                     void* out, float* lse, int32_t* tile_map, hipStream_t stream);
+
+int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
+                 const pyr_shape& shape, int32_t w, float scale_log2, float* scores, hipStream_t stream);
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? PYR_OK : PYR_ERR_LAUNCH; }
+
+}  // namespace pyr

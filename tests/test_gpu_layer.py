@@ -1,0 +1,134 @@
+"""GPU parity of the attention, score and whole-layer entry points against the float64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import pyr_oracle as orc
+from paper_2405_12532_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+F64 = synth.bf16_bits_to_f64
+
+
+def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=None):
+    x = synth.make_inputs(wl, layer=layer) if x is None else x
+    hid = x.get("hidden") if hidden else None
+    res = lib.prefill_layer_from_numpy(x, wl.w, hidden=hid, softmax_scale=scale)
+    ref = orc.prefill_layer(F64(x["q"]), F64(x["k"]), F64(x["v"]), x["seq_offsets"], wl.w, x["keep_len"],
+                            scale=scale if scale > 0 else None, out_rows=out_rows)
+    mx, mean = parity.check_out(res["out"], ref, x["seq_offsets"], F64)
+    rel = parity.check_scores(res["scores"], ref)
+    same, swapped = parity.check_index_sets(res["kept_idx"], ref, x["seq_offsets"], x["keep_len"], wl.w)
+    assert res["out_offsets"].tolist() == ref["out_offsets"].tolist()
+    kidx = res["kept_idx"]
+    assert np.array_equal(res["k_out"], x["k"][kidx]), "gathered K must be bit-exact given the indices"
+    assert np.array_equal(res["v_out"], x["v"][kidx])
+    if hid is not None:
+        assert np.array_equal(res["hidden_out"], hid[kidx])
+    # per-sequence score mass is one (all S columns are emitted)
+    for b in range(wl.n_seqs):
+        r0, r1 = x["seq_offsets"][b], x["seq_offsets"][b + 1]
+        if r1 > r0:
+            assert abs(float(res["scores"][r0:r1].astype(np.float64).sum()) - 1.0) < 1e-4
+    print(f"[{wl.name}] out max {mx:.2e} mean {mean:.2e}; score rel {rel:.2e}; "
+          f"identical index sets {same}/{wl.n_seqs}, swapped in band {swapped}")
+    return res, ref, x
+
+
+def sample_rows(wl, n_random, seed, full_seqs=()):
+    """Per sequence: every row for `full_seqs`, else first/last rows, tile edges and a random sample."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for b, S in enumerate(wl.seq_lens):
+        if b in full_seqs:
+            rows.append(np.arange(S))
+            continue
+        fixed = [0, 1, 31, 32, 63, 64, 255, 256, 257, S // 2, S - wl.w - 1, S - wl.w, S - 2, S - 1]
+        fixed = [r for r in fixed if 0 <= r < S]
+        rnd = rng.integers(0, S, size=n_random).tolist()
+        rows.append(np.unique(np.asarray(fixed + rnd, dtype=np.int64)))
+    return rows
+
+
+# --------------------------------------------------------------------------- small, complete
+def test_cfg1_complete(lib):
+    """Config 1 at full size: batch 1, 8 heads, d 64, S 256, w 16, keep 128."""
+    run_and_check(lib, synth.workload("cfg1"))
+
+
+@pytest.mark.parametrize("lens,Hq,Hkv,d,w", [
+    ((300, 97, 513), 4, 2, 128, 32),          # ragged, several key tiles, ragged tails, GQA 2
+    ((1, 2, 31, 33, 64, 65), 2, 2, 64, 16),   # tiny sequences, S<w, S==w+..., d 64
+    ((700,), 8, 1, 128, 64),                  # GQA 8 (all query heads on one KV head)
+    ((256, 512, 768), 8, 8, 64, 48),          # exact multiples of the block height, 8 KV heads (XCD map)
+    ((1000, 40), 16, 8, 128, 100),            # window not a multiple of 32
+])
+def test_small_shapes_complete(lib, lens, Hq, Hkv, d, w):
+    wl = synth.shrunk(synth.workload("cfg2"), lens, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, w=w, hidden_dim=128)
+    run_and_check(lib, wl)
+
+
+def test_custom_softmax_scale(lib):
+    wl = synth.shrunk(synth.workload("cfg2"), (333, 100), n_q_heads=4, n_kv_heads=4, head_dim=64, w=20)
+    run_and_check(lib, wl, scale=0.2)
+
+
+def test_degenerate_keep_lengths(lib):
+    """keep everything (identity), keep only the window ("local"), sequences shorter than the window."""
+    base = synth.shrunk(synth.workload("cfg2"), (300, 300, 10, 64), n_q_heads=4, n_kv_heads=2, head_dim=64, w=64,
+                        hidden_dim=64)
+    x = synth.make_inputs(base)
+    x["keep_len"] = np.asarray([300, 64, 10, 64], dtype=np.int32)
+    res, ref, _ = run_and_check(lib, base, x=x)
+    assert res["kept_idx"][:300].tolist() == list(range(300))
+    assert res["kept_idx"][300:364].tolist() == list(range(300 + 236, 600))
+
+
+def test_zero_keys_uniform_attention_full_tie(lib):
+    """K = 0: every causal row is uniform, out = prefix means of V, scores are the harmonic
+    tail (closed form), and context scores before the window are all equal, so the tie rule
+    alone decides the selection: the lowest positions win."""
+    wl = synth.shrunk(synth.workload("cfg1"), (400,), n_q_heads=4, n_kv_heads=4, head_dim=64, w=16, keep_fixed=100)
+    x = synth.make_inputs(wl)
+    x["k"][:] = 0
+    res, ref, _ = run_and_check(lib, wl, x=x)
+    S, L = 400, 16
+    closed = np.array([sum(1.0 / (i + 1) for i in range(max(t, S - L), S)) / L for t in range(S)])
+    np.testing.assert_allclose(res["scores"], closed, rtol=1e-4)
+    assert res["kept_idx"].tolist() == list(range(84)) + list(range(384, 400))
+
+
+def test_layer_is_bit_reproducible(lib):
+    wl = synth.shrunk(synth.workload("cfg2"), (900, 333), n_q_heads=8, n_kv_heads=8, head_dim=128, w=64)
+    x = synth.make_inputs(wl)
+    a = lib.prefill_layer_from_numpy(x, wl.w)
+    b = lib.prefill_layer_from_numpy(x, wl.w)
+    for name in ("out", "scores", "kept_idx", "lse"):
+        assert np.array_equal(a[name], b[name]), name
+
+
+# --------------------------------------------------------------------------- workload shapes
+def test_cfg2_shape(lib):
+    """Config 2 at full size (8 x 2048, 32 heads, d 128, w 64, keep 0.7): scores, selection and
+    gathers complete; attention output on all rows of sequence 0 and sampled rows elsewhere."""
+    wl = synth.workload("cfg2")
+    res, ref, x = run_and_check(lib, wl, out_rows=sample_rows(wl, 24, 1, full_seqs=(0,)))
+    off = x["seq_offsets"]
+    for b in range(wl.n_seqs):
+        heavy_ctx = [int(t + off[b]) for t in x["heavy"][b] if t < 2048 - wl.w]
+        assert set(heavy_ctx) <= set(res["kept_idx"].tolist()), "planted heavy keys must be retained"
+
+
+def test_cfg4_ragged_reduced(lib):
+    """Config 4's recipe (40 heads, d 128, ragged lengths, keep 0.6) on 6 of its sequences, lengths / 4."""
+    full = synth.workload("cfg4")
+    lens = [max(64, s // 4) for s in full.seq_lens[:6]]
+    wl = synth.shrunk(full, lens)
+    run_and_check(lib, wl, out_rows=sample_rows(wl, 16, 2))
+
+
+def test_cfg5_gqa_reduced(lib):
+    """Config 5's recipe (64 query / 8 KV heads, w 128, keep 0.5) at S 4096, batch 2."""
+    wl = synth.shrunk(synth.workload("cfg5"), (4096, 4096))
+    run_and_check(lib, wl, out_rows=sample_rows(wl, 8, 3))

@@ -13,11 +13,16 @@
 // exchange with lane^32 completes them) and rescaling the output is a per-lane multiply.
 // The output is accumulated transposed too,  O^T += V^T P^T,  whose B operand P^T is exactly
 // what the lane already holds once the K rows of a 32-key sub-tile are fed in the order
-// "bits 2 and 3 of the row number swapped".  V is transposed on its way into LDS.
+// "bits 2 and 3 of the row number swapped".  V sits in LDS row-major like K; its A-operand
+// fragments (8 keys of one head-dim column per lane) come out of LDS already transposed
+// through ds_read_b64_tr_b16, so no transposition pass and no 2-byte LDS traffic exists.
 //
 // Numerics: bf16 products, fp32 accumulation, fp32 online softmax in base 2 with the scale
 // folded into one FMA per logit; probabilities are rounded to bf16 for the PV product while
-// the softmax denominator is summed from the unrounded fp32 values.
+// the softmax denominator is summed from the unrounded fp32 values.  The running reference
+// of the exponent is only moved (and the output rescaled) when some row's maximum grows by
+// more than 2^8 over it: probabilities then stay below 2^8, exact in fp32 and as precise in
+// bf16 as any other magnitude, and almost every tile skips the rescale.
 #include "pyr_internal.h"
 
 namespace pyr {
@@ -28,14 +33,33 @@ constexpr int kBN = 64;                    // key positions per LDS tile
 template <int D>
 struct Tile {
     static constexpr int kKStride = D + 8;         // bf16 elements per K row (+16 B: conflict-free b128 reads)
-    static constexpr int kVStride = kBN + 8;       // bf16 elements per V^T row
+    static constexpr int kVStride = D + 32;        // bf16 elements per V row (+64 B: 4 rows x 64 B tile the banks)
     static constexpr int kKElems = kBN * kKStride;
-    static constexpr int kVElems = D * kVStride;
+    static constexpr int kVElems = kBN * kVStride;
     static constexpr int kStageElems = kKElems + kVElems;
     static constexpr size_t kLdsBytes = 2 * (size_t)kStageElems * sizeof(uint16_t);
 };
 
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+// v_permlane32_swap(x, x): result 0 holds lanes 0..31 of x in both halves, result 1 holds
+// lanes 32..63 of x in both halves; combining the two gives "own op other half" in every lane.
+__device__ __forceinline__ float max_with_other_half(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Inside every group of 16 lanes, lane j receives
+// element (j & 3) of the 8-byte words addressed by lanes (j >> 2), 4 + (j >> 2), 8 + (j >> 2)
+// and 12 + (j >> 2), in this order.
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
+}
 
 // prefix sums of the number of query tiles per sequence (ragged batches only)
 __global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
@@ -75,7 +99,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     constexpr int kKSteps = D / 16;               // MFMA k-steps over the head dimension
     constexpr int kDTiles = D / 32;               // 32-row tiles of O^T
     constexpr int kChunks = D / 8;                // 16-byte chunks per K/V row
-    constexpr int kItems = kChunks * (kBN / 4);   // (chunk, 4-key group) load items per matrix and tile
+    constexpr int kItemsMat = kChunks * (kBN / 4);   // (chunk, 4-key group) load items per matrix and tile
+    constexpr int kItems = 2 * kItemsMat;            // K items first, then V items
     constexpr int kItemsPerThread = (kItems + kNT - 1) / kNT;
     static_assert(kBM == kAttnBlockRows, "the host tile map assumes this block height");
 
@@ -146,60 +171,57 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
             for (int r = 0; r < 16; ++r) oacc[qb][dt][r] = 0.f;
     }
 
-    // ---- K/V tile movement: global -> registers (one tile ahead) -> LDS
-    u32x4 kreg[kItemsPerThread][4], vreg[kItemsPerThread][4];
-    const uint16_t* kbase_ptr = k + ((size_t)row0 * n_kv_heads + kvh) * D;
-    const uint16_t* vbase_ptr = v + ((size_t)row0 * n_kv_heads + kvh) * D;
+    // ---- K/V tile movement: global -> registers (one tile ahead) -> LDS, 16 bytes per access
+    u32x4 kvreg[kItemsPerThread][4];
     const size_t tok_stride = (size_t)n_kv_heads * D;
+    const size_t head_off = ((size_t)row0 * n_kv_heads + kvh) * D;
 
     auto load_tile = [&](int t) {
 #pragma unroll
         for (int it = 0; it < kItemsPerThread; ++it) {
             const int item = tid + it * kNT;
             if (kItems % kNT == 0 || item < kItems) {
-                const int dc = item % kChunks, kq = item / kChunks;
+                const uint16_t* base = (item < kItemsMat ? k : v) + head_off;
+                const int im = item % kItemsMat;
+                const int dc = im % kChunks, kq = im / kChunks;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int key = min(t * kBN + 4 * kq + e, S - 1);
-                    kreg[it][e] = *(const u32x4*)(kbase_ptr + key * tok_stride + dc * 8);
-                    vreg[it][e] = *(const u32x4*)(vbase_ptr + key * tok_stride + dc * 8);
+                    kvreg[it][e] = *(const u32x4*)(base + key * tok_stride + dc * 8);
                 }
             }
         }
     };
     auto store_tile = [&](int stage) {
         uint16_t* Ks = smem + stage * T::kStageElems;
-        uint16_t* Vt = Ks + T::kKElems;
+        uint16_t* Vs = Ks + T::kKElems;
 #pragma unroll
         for (int it = 0; it < kItemsPerThread; ++it) {
             const int item = tid + it * kNT;
             if (kItems % kNT == 0 || item < kItems) {
-                const int dc = item % kChunks, kq = item / kChunks;
+                const bool is_k = item < kItemsMat;
+                const int im = item % kItemsMat;
+                const int dc = im % kChunks, kq = im / kChunks;
+                uint16_t* dst = is_k ? Ks + 4 * kq * T::kKStride : Vs + 4 * kq * T::kVStride;
+                const int stride = is_k ? T::kKStride : T::kVStride;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    *(u32x4*)(Ks + (4 * kq + e) * T::kKStride + dc * 8) = kreg[it][e];
-                // 4 keys x 8 dims  ->  8 rows (dims) x 4 keys
-#pragma unroll
-                for (int dd = 0; dd < 8; ++dd) {
-                    const int wsel = dd >> 1;
-                    uint32_t e0 = vreg[it][0][wsel], e1 = vreg[it][1][wsel], e2 = vreg[it][2][wsel], e3 = vreg[it][3][wsel];
-                    u32x2 pk;
-                    if (dd & 1) { pk[0] = (e0 >> 16) | (e1 & 0xffff0000u); pk[1] = (e2 >> 16) | (e3 & 0xffff0000u); }
-                    else        { pk[0] = (e0 & 0xffffu) | (e1 << 16);     pk[1] = (e2 & 0xffffu) | (e3 << 16); }
-                    *(u32x2*)(Vt + (dc * 8 + dd) * T::kVStride + 4 * kq) = pk;
-                }
+                for (int e = 0; e < 4; ++e) *(u32x4*)(dst + e * stride + dc * 8) = kvreg[it][e];
             }
         }
     };
 
     // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
     const int krow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
+    // V fragment addressing for the transposing read: this lane supplies the 8-byte word at
+    // key (8*gl + ((lane & 15) >> 2)) (+4 for the second read), head-dim column
+    // 16*((lane >> 4) & 1) + 4*(lane & 3) of the 16-key step / 32-column tile being fetched.
+    const int v_lane_off = (8 * gl + ((lane & 15) >> 2)) * T::kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
     // softmax + PV for the q-blocks [QB0, QB) of this wavefront on the tile in `stage`
     auto compute_tile = [&](int t, int stage, auto first_active) {
         constexpr int kFirst = decltype(first_active)::value;
         const uint16_t* Ks = smem + stage * T::kStageElems;
-        const uint16_t* Vt = Ks + T::kKElems;
+        const uint16_t* Vs = Ks + T::kKElems;
         const int key0 = t * kBN;
 
         f32x16 sacc[QB][2];
@@ -236,14 +258,18 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
                         if (key > qrow || key >= S) sacc[qb][sk][r] = -INFINITY;
                     }
             }
-            float mx = sacc[qb][0][0];
+            float mx = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
 #pragma unroll
             for (int sk = 0; sk < 2; ++sk)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[qb][sk][r]);
-            mx = fmaxf(mx, other_half(mx));
-            const float m_new = fmaxf(m_run[qb], mx);
-            if (__ballot(m_new != m_run[qb]) != 0) {
+                for (int r = 1; r < 16; r += 2) {
+                    const float nxt = r + 1 < 16 ? sacc[qb][sk][r + 1] : sacc[qb][sk][r];
+                    mx = fmaxf(fmaxf(mx, sacc[qb][sk][r]), nxt);          // v_max3_f32
+                }
+            mx = max_with_other_half(mx);
+            // move the reference only when some row outgrew it by more than 2^8
+            if (__ballot((mx - m_run[qb]) * c > 8.0f) != 0) {
+                const float m_new = fmaxf(m_run[qb], mx);
                 const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
                 l_run[qb] *= alpha;
 #pragma unroll
@@ -252,7 +278,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
                     for (int r = 0; r < 16; ++r) oacc[qb][dt][r] *= alpha;
                 m_run[qb] = m_new;
             }
-            const float mc = m_new * c;
+            const float mc = m_run[qb] * c;
             float lsum = 0.f;
 #pragma unroll
             for (int sk = 0; sk < 2; ++sk)
@@ -272,10 +298,13 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
 
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt) {
-            const uint16_t* vrow_ptr = Vt + (32 * dt + li) * T::kVStride + 8 * gl;
+            const uint16_t* vptr = Vs + v_lane_off + 32 * dt;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                const bf16x8 vf = *(const bf16x8*)(vrow_ptr + 16 * ks);
+                const s16x4 lo = lds_read_tr(vptr + (16 * ks) * T::kVStride);
+                const s16x4 hi = lds_read_tr(vptr + (16 * ks + 4) * T::kVStride);
+                const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
 #pragma unroll
                 for (int qb = kFirst; qb < QB; ++qb)
                     oacc[qb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], oacc[qb][dt], 0, 0, 0);
@@ -303,7 +332,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     // ---- epilogue: normalise, round to bf16, store; log2 of the denominator for the score pass
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float ltot = l_run[qb] + other_half(l_run[qb]);
+        const float ltot = sum_with_other_half(l_run[qb]);
         const float inv = 1.0f / ltot;
         const int qrow = qlo[qb] + li;
         if (qrow < S) {
@@ -327,7 +356,7 @@ template <int D>
 int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
                        const pyr_shape& s, int32_t uniform_len, int64_t total_q_tiles, float c,
                        void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
-    constexpr int QB = 2, NW = 4;
+    constexpr int QB = 1, NW = 8;
     auto kern = attention_kernel<D, QB, NW>;
     static bool attr_done = false;   // benign race: the attribute call is idempotent
     if (!attr_done) {

@@ -1,11 +1,11 @@
 // Causal softmax attention over packed, ragged sequences (Algorithm 1, "compute attention
 // weights of KV", applied to V), flash style: the S x S weight matrix never exists.
 //
-// Work split.  One workgroup owns kBM = 256 consecutive query positions of one (sequence,
-// query head); its wavefronts each own 32-row blocks.  With two blocks per wavefront, wave
-// i takes blocks i and 7-i, so every wavefront sees the same number of causal key tiles.
-// Keys/values stream through LDS in tiles of 64 positions, double buffered, loaded with
-// 16-byte accesses one tile ahead of the arithmetic.
+// Work split.  One workgroup owns kAttnBlockRows consecutive query positions of one
+// (sequence, query head); each of its wavefronts owns 32 of them.  Keys/values stream
+// through LDS in tiles of 64 positions, double buffered, loaded with 16-byte accesses one
+// tile ahead of the arithmetic.  Two workgroups share a compute unit, so each SIMD holds two
+// free-running wavefronts: one can feed the matrix pipe while the other does softmax.
 //
 // MFMA mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts).  The kernel computes the
 // TRANSPOSED logits  S^T = K Q^T  (keys x queries): in the accumulator layout a lane then
@@ -86,27 +86,27 @@ __global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t* __restric
     if (tid == 1023) tile_map[n_seqs] = part[1023];
 }
 
-template <int D, int QB, int NW>
-__global__ __launch_bounds__(NW * 64) void attention_kernel(
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ tile_map,
     int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds, float c,
     uint16_t* __restrict__ out, float* __restrict__ lse) {
     using T = Tile<D>;
     constexpr int kNT = NW * 64;
-    constexpr int kBM = NW * QB * 32;
-    constexpr int kNSub = NW * QB;
-    constexpr int kKSteps = D / 16;               // MFMA k-steps over the head dimension
-    constexpr int kDTiles = D / 32;               // 32-row tiles of O^T
-    constexpr int kChunks = D / 8;                // 16-byte chunks per K/V row
+    constexpr int kBM = NW * 32;
+    constexpr int kKSteps = D / 16;                  // MFMA k-steps over the head dimension
+    constexpr int kDTiles = D / 32;                  // 32-row tiles of O^T
+    constexpr int kChunks = D / 8;                   // 16-byte chunks per K/V row
     constexpr int kItemsMat = kChunks * (kBN / 4);   // (chunk, 4-key group) load items per matrix and tile
     constexpr int kItems = 2 * kItemsMat;            // K items first, then V items
     constexpr int kItemsPerThread = (kItems + kNT - 1) / kNT;
-    static_assert(kBM == kAttnBlockRows, "the host tile map assumes this block height");
+    constexpr int kGroup = 4;                        // LDS fragments fetched ahead of the MFMAs that eat them
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31;                     // row (A operand) / column (B, C) inside a 32-wide tile
     const int gl = lane >> 5;                     // which half of the k-slots / accumulator rows
 
@@ -144,32 +144,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
     const int S = seq_offsets[b + 1] - row0;
     const int q_base = q_tile * kBM;
     const int n_kv_tiles = (min(S, q_base + kBM) + kBN - 1) / kBN;
-
-    int qlo[QB];
-    if (QB == 2) { qlo[0] = q_base + 32 * wave; qlo[QB - 1] = q_base + 32 * (kNSub - 1 - wave); }
-    else         { qlo[0] = q_base + 32 * wave; }
-
-    // ---- query fragments stay in registers for the whole sweep (B operand of S^T = K Q^T)
-    bf16x8 qf[QB][kKSteps];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int row = min(qlo[qb] + li, S - 1);
-        const uint16_t* src = q + ((size_t)(row0 + row) * n_q_heads + h) * D + 8 * gl;
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) qf[qb][ks] = *(const bf16x8*)(src + 16 * ks);
-    }
-
-    f32x16 oacc[QB][kDTiles];
-    float m_run[QB], l_run[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[qb][dt][r] = 0.f;
-    }
+    const int qlo = q_base + 32 * wave;           // first query position of this wavefront
+    const int qrow = qlo + li;                    // this lane's query position
 
     // ---- K/V tile movement: global -> registers (one tile ahead) -> LDS, 16 bytes per access
     u32x4 kvreg[kItemsPerThread][4];
@@ -210,154 +186,178 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(
         }
     };
 
+    // ---- query fragments stay in registers for the whole sweep (B operand of S^T = K Q^T)
+    bf16x8 qf[kKSteps];
+    {
+        const int row = min(qrow, S - 1);
+        const uint16_t* src = q + ((size_t)(row0 + row) * n_q_heads + h) * D + 8 * gl;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
+    }
+    load_tile(0);
+    // The fragments must have landed before the sweep starts: a load still pending at the loop
+    // head would make every iteration wait for ALL outstanding loads, the prefetch included.
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+    store_tile(0);
+
+    f32x16 oacc[kDTiles];
+#pragma unroll
+    for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
     // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
     const int krow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
+    const int k_lane_off = krow * T::kKStride + 8 * gl;
     // V fragment addressing for the transposing read: this lane supplies the 8-byte word at
     // key (8*gl + ((lane & 15) >> 2)) (+4 for the second read), head-dim column
     // 16*((lane >> 4) & 1) + 4*(lane & 3) of the 16-key step / 32-column tile being fetched.
     const int v_lane_off = (8 * gl + ((lane & 15) >> 2)) * T::kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-    // softmax + PV for the q-blocks [QB0, QB) of this wavefront on the tile in `stage`
-    auto compute_tile = [&](int t, int stage, auto first_active) {
-        constexpr int kFirst = decltype(first_active)::value;
-        const uint16_t* Ks = smem + stage * T::kStageElems;
-        const uint16_t* Vs = Ks + T::kKElems;
+    auto compute_tile = [&](int t, int stage) {
+        const uint16_t* Ks = smem + stage * T::kStageElems + k_lane_off;
+        const uint16_t* Vs = smem + stage * T::kStageElems + T::kKElems + v_lane_off;
         const int key0 = t * kBN;
 
-        f32x16 sacc[QB][2];
+        // ---- S^T = K Q^T for the two 32-key sub-tiles; fragments are fetched kGroup ahead
+        constexpr int kNK = 2 * kKSteps;
+        auto k_frag = [&](int i) { return *(const bf16x8*)(Ks + (32 * (i / kKSteps)) * T::kKStride + 16 * (i % kKSteps)); };
+        f32x16 sacc[2];
 #pragma unroll
-        for (int qb = kFirst; qb < QB; ++qb)
+        for (int sk = 0; sk < 2; ++sk)
 #pragma unroll
-            for (int sk = 0; sk < 2; ++sk)
+            for (int r = 0; r < 16; ++r) sacc[sk][r] = 0.f;
+        bf16x8 kf[kNK];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[qb][sk][r] = 0.f;
-
+        for (int i = 0; i < kGroup; ++i) kf[i] = k_frag(i);
 #pragma unroll
-        for (int sk = 0; sk < 2; ++sk) {
-            const uint16_t* krow_ptr = Ks + (32 * sk + krow) * T::kKStride + 8 * gl;
+        for (int g0 = 0; g0 < kNK; g0 += kGroup) {
+            if (g0 + kGroup < kNK) {
 #pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) {
-                const bf16x8 kf = *(const bf16x8*)(krow_ptr + 16 * ks);
-#pragma unroll
-                for (int qb = kFirst; qb < QB; ++qb)
-                    sacc[qb][sk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sacc[qb][sk], 0, 0, 0);
+                for (int i = 0; i < kGroup; ++i) kf[g0 + kGroup + i] = k_frag(g0 + kGroup + i);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = g0; i < g0 + kGroup; ++i)
+                sacc[i / kKSteps] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i % kKSteps], sacc[i / kKSteps], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
 
-        bf16x8 pf[QB][4];
+        // first V fragments travel while the softmax runs
+        constexpr int kNV = kDTiles * 4;
+        auto v_frag = [&](int i) {
+            const uint16_t* p = Vs + (16 * (i % 4)) * T::kVStride + 32 * (i / 4);
+            const s16x4 lo = lds_read_tr(p);
+            const s16x4 hi = lds_read_tr(p + 4 * T::kVStride);
+            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+        bf16x8 vf[kNV];
 #pragma unroll
-        for (int qb = kFirst; qb < QB; ++qb) {
-            const int qrow = qlo[qb] + li;
-            const bool need_mask = (key0 + kBN - 1 > qlo[qb]) || (key0 + kBN > S);   // wave-uniform
-            if (need_mask) {
-#pragma unroll
-                for (int sk = 0; sk < 2; ++sk)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = key0 + 32 * sk + 16 * (r >> 3) + 8 * gl + (r & 7);
-                        if (key > qrow || key >= S) sacc[qb][sk][r] = -INFINITY;
-                    }
-            }
-            float mx = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
-#pragma unroll
-            for (int sk = 0; sk < 2; ++sk)
-#pragma unroll
-                for (int r = 1; r < 16; r += 2) {
-                    const float nxt = r + 1 < 16 ? sacc[qb][sk][r + 1] : sacc[qb][sk][r];
-                    mx = fmaxf(fmaxf(mx, sacc[qb][sk][r]), nxt);          // v_max3_f32
-                }
-            mx = max_with_other_half(mx);
-            // move the reference only when some row outgrew it by more than 2^8
-            if (__ballot((mx - m_run[qb]) * c > 8.0f) != 0) {
-                const float m_new = fmaxf(m_run[qb], mx);
-                const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c);
-                l_run[qb] *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[qb][dt][r] *= alpha;
-                m_run[qb] = m_new;
-            }
-            const float mc = m_run[qb] * c;
-            float lsum = 0.f;
-#pragma unroll
-            for (int sk = 0; sk < 2; ++sk)
-#pragma unroll
-                for (int a = 0; a < 2; ++a) {
-                    bf16x8 pk;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][sk][8 * a + e], c, -mc));
-                        lsum += p;
-                        pk[e] = (__bf16)p;
-                    }
-                    pf[qb][2 * sk + a] = pk;
-                }
-            l_run[qb] += lsum;
-        }
+        for (int i = 0; i < kGroup; ++i) vf[i] = v_frag(i);
+        __builtin_amdgcn_sched_barrier(0);
 
+        // ---- online softmax of this lane's query column (32 of the 64 keys; lane^32 has the rest)
+        const bool need_mask = (key0 + kBN - 1 > qlo) || (key0 + kBN > S);   // wave-uniform
+        if (need_mask) {
 #pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt) {
-            const uint16_t* vptr = Vs + v_lane_off + 32 * dt;
+            for (int sk = 0; sk < 2; ++sk)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const s16x4 lo = lds_read_tr(vptr + (16 * ks) * T::kVStride);
-                const s16x4 hi = lds_read_tr(vptr + (16 * ks + 4) * T::kVStride);
-                const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + 32 * sk + 16 * (r >> 3) + 8 * gl + (r & 7);
+                    if (key > qrow || key >= S) sacc[sk][r] = -INFINITY;
+                }
+        }
+        float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
-                for (int qb = kFirst; qb < QB; ++qb)
-                    oacc[qb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], oacc[qb][dt], 0, 0, 0);
+        for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+            for (int r = 1; r < 16; r += 2) {
+                const float nxt = r + 1 < 16 ? sacc[sk][r + 1] : sacc[sk][r];
+                mx = fmaxf(fmaxf(mx, sacc[sk][r]), nxt);          // v_max3_f32
             }
+        mx = max_with_other_half(mx);
+        // move the reference only when some row outgrew it by more than 2^8
+        if (__ballot((mx - m_run) * c > 8.0f) != 0) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+            m_run = m_new;
+        }
+        const float mc = m_run * c;
+        float lsum = 0.f;
+        bf16x8 pf[4];
+#pragma unroll
+        for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                bf16x8 pk;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[sk][8 * a + e], c, -mc));
+                    lsum += p;
+                    pk[e] = (__bf16)p;
+                }
+                pf[2 * sk + a] = pk;
+            }
+        l_run += lsum;
+
+        // ---- O^T += V^T P^T
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g0 = 0; g0 < kNV; g0 += kGroup) {
+            if (g0 + kGroup < kNV) {
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) vf[g0 + kGroup + i] = v_frag(g0 + kGroup + i);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = g0; i < g0 + kGroup; ++i)
+                oacc[i / 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], pf[i % 4], oacc[i / 4], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     // ---- main sweep over the key tiles
-    load_tile(0);
-    store_tile(0);
     for (int t = 0; t < n_kv_tiles; ++t) {
         __syncthreads();
         const bool more = t + 1 < n_kv_tiles;
         if (more) load_tile(t + 1);
-        const int key0 = t * kBN;
-        // a q-block takes part while some key of the tile is visible to its last row
-        if (QB == 2 && key0 <= qlo[0] + 31) {
-            compute_tile(t, t & 1, std::integral_constant<int, 0>{});
-        } else if (key0 <= qlo[QB - 1] + 31) {
-            compute_tile(t, t & 1, std::integral_constant<int, QB - 1>{});
-        }
+        // the wavefront takes part while some key of the tile is visible to its last row
+        if (t * kBN <= qlo + 31) compute_tile(t, t & 1);
         if (more) store_tile((t + 1) & 1);
     }
 
     // ---- epilogue: normalise, round to bf16, store; log2 of the denominator for the score pass
+    const float ltot = sum_with_other_half(l_run);
+    const float inv = 1.0f / ltot;
+    if (qrow < S) {
+        uint16_t* dst = out + ((size_t)(row0 + qrow) * n_q_heads + h) * D + 4 * gl;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const float ltot = sum_with_other_half(l_run[qb]);
-        const float inv = 1.0f / ltot;
-        const int qrow = qlo[qb] + li;
-        if (qrow < S) {
-            uint16_t* dst = out + ((size_t)(row0 + qrow) * n_q_heads + h) * D + 4 * gl;
+        for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
-            for (int dt = 0; dt < kDTiles; ++dt)
+            for (int a = 0; a < 4; ++a) {
+                bf16x4 o4;
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    bf16x4 o4;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[qb][dt][4 * a + e] * inv);
-                    *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
-                }
-            if (lse != nullptr && gl == 0)
-                lse[(size_t)(row0 + qrow) * n_q_heads + h] = m_run[qb] * c + __builtin_amdgcn_logf(ltot);
-        }
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][4 * a + e] * inv);
+                *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
+            }
+        if (lse != nullptr && gl == 0)
+            lse[(size_t)(row0 + qrow) * n_q_heads + h] = m_run * c + __builtin_amdgcn_logf(ltot);
     }
 }
 
-template <int D>
+template <int D, int NW>
 int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
                        const pyr_shape& s, int32_t uniform_len, int64_t total_q_tiles, float c,
                        void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
-    constexpr int QB = 1, NW = 8;
-    auto kern = attention_kernel<D, QB, NW>;
+    static_assert(NW * 32 == kAttnBlockRows, "the host tile count assumes this block height");
+    auto kern = attention_kernel<D, NW>;
     static bool attr_done = false;   // benign race: the attribute call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -386,9 +386,9 @@ int launch_attention(const void* q, const void* k, const void* v, const int32_t*
                      const pyr_shape& shape, int32_t uniform_len, int64_t total_q_tiles, float scale_log2,
                      void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
     if (shape.head_dim == 128)
-        return launch_attention_d<128>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
+        return launch_attention_d<128, kAttnBlockRows / 32>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
                                        out, lse, tile_map, stream);
-    return launch_attention_d<64>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
+    return launch_attention_d<64, kAttnBlockRows / 32>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
                                   out, lse, tile_map, stream);
 }
 

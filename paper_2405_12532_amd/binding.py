@@ -10,7 +10,8 @@ from __future__ import annotations
 import ctypes
 import os
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpyr.so")
+# PYR_LIB may point at another build of the same ABI (tuning experiments); default: the in-tree library
+_LIB_PATH = os.environ.get("PYR_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpyr.so")
 _lib = None
 
 

@@ -101,7 +101,6 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
     constexpr int kItemsMat = kChunks * (kBN / 4);   // (chunk, 4-key group) load items per matrix and tile
     constexpr int kItems = 2 * kItemsMat;            // K items first, then V items
     constexpr int kItemsPerThread = (kItems + kNT - 1) / kNT;
-    constexpr int kGroup = 4;                        // LDS fragments fetched ahead of the MFMAs that eat them
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
 
@@ -216,111 +215,159 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
     // 16*((lane >> 4) & 1) + 4*(lane & 3) of the 16-key step / 32-column tile being fetched.
     const int v_lane_off = (8 * gl + ((lane & 15) >> 2)) * T::kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
+    // One 64-key tile.  The two 32-key halves are two independent instruction streams that
+    // are overlapped inside the wavefront: while the matrix pipe runs QK^T of the second half
+    // the vector pipe exponentiates the first, and while it runs P V of the first half the
+    // vector pipe exponentiates the second.
     auto compute_tile = [&](int t, int stage) {
         const uint16_t* Ks = smem + stage * T::kStageElems + k_lane_off;
         const uint16_t* Vs = smem + stage * T::kStageElems + T::kKElems + v_lane_off;
         const int key0 = t * kBN;
 
-        // ---- S^T = K Q^T for the two 32-key sub-tiles; fragments are fetched kGroup ahead
-        constexpr int kNK = 2 * kKSteps;
-        auto k_frag = [&](int i) { return *(const bf16x8*)(Ks + (32 * (i / kKSteps)) * T::kKStride + 16 * (i % kKSteps)); };
-        f32x16 sacc[2];
-#pragma unroll
-        for (int sk = 0; sk < 2; ++sk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[sk][r] = 0.f;
-        bf16x8 kf[kNK];
-#pragma unroll
-        for (int i = 0; i < kGroup; ++i) kf[i] = k_frag(i);
-#pragma unroll
-        for (int g0 = 0; g0 < kNK; g0 += kGroup) {
-            if (g0 + kGroup < kNK) {
-#pragma unroll
-                for (int i = 0; i < kGroup; ++i) kf[g0 + kGroup + i] = k_frag(g0 + kGroup + i);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = g0; i < g0 + kGroup; ++i)
-                sacc[i / kKSteps] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i % kKSteps], sacc[i / kKSteps], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-
-        // first V fragments travel while the softmax runs
-        constexpr int kNV = kDTiles * 4;
-        auto v_frag = [&](int i) {
-            const uint16_t* p = Vs + (16 * (i % 4)) * T::kVStride + 32 * (i / 4);
+        auto k_frag = [&](int half, int ks) { return *(const bf16x8*)(Ks + (32 * half) * T::kKStride + 16 * ks); };
+        auto v_frag = [&](int dt, int ks) {
+            const uint16_t* p = Vs + (16 * ks) * T::kVStride + 32 * dt;
             const s16x4 lo = lds_read_tr(p);
             const s16x4 hi = lds_read_tr(p + 4 * T::kVStride);
             return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         };
-        bf16x8 vf[kNV];
-#pragma unroll
-        for (int i = 0; i < kGroup; ++i) vf[i] = v_frag(i);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- online softmax of this lane's query column (32 of the 64 keys; lane^32 has the rest)
-        const bool need_mask = (key0 + kBN - 1 > qlo) || (key0 + kBN > S);   // wave-uniform
-        if (need_mask) {
-#pragma unroll
-            for (int sk = 0; sk < 2; ++sk)
+        // row maximum of one half (own 16 keys and the 16 of lane^32), masked on diagonal tiles
+        auto half_max = [&](f32x16& sv, int half) {
+            const int kbase = key0 + 32 * half;
+            if ((kbase + 31 > qlo) || (kbase + 32 > S)) {            // wave-uniform
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int key = key0 + 32 * sk + 16 * (r >> 3) + 8 * gl + (r & 7);
-                    if (key > qrow || key >= S) sacc[sk][r] = -INFINITY;
+                    const int key = kbase + 16 * (r >> 3) + 8 * gl + (r & 7);
+                    if (key > qrow || key >= S) sv[r] = -INFINITY;
                 }
-        }
-        float mx = fmaxf(sacc[0][0], sacc[1][0]);
-#pragma unroll
-        for (int sk = 0; sk < 2; ++sk)
+            }
+            float mx = sv[0];
 #pragma unroll
             for (int r = 1; r < 16; r += 2) {
-                const float nxt = r + 1 < 16 ? sacc[sk][r + 1] : sacc[sk][r];
-                mx = fmaxf(fmaxf(mx, sacc[sk][r]), nxt);          // v_max3_f32
+                const float nxt = r + 1 < 16 ? sv[r + 1] : sv[r];
+                mx = fmaxf(fmaxf(mx, sv[r]), nxt);                  // v_max3_f32
             }
-        mx = max_with_other_half(mx);
-        // move the reference only when some row outgrew it by more than 2^8
-        if (__ballot((mx - m_run) * c > 8.0f) != 0) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-            l_run *= alpha;
+            return max_with_other_half(mx);
+        };
+        // p = 2^(c s - c m) for one half: fp32 row sum, bf16 fragments for the PV product
+        auto half_exp = [&](const f32x16& sv, bf16x8& p0, bf16x8& p1) {
+            const float mc = m_run * c;
+            float lsum = 0.f;
 #pragma unroll
-            for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-            m_run = m_new;
-        }
-        const float mc = m_run * c;
-        float lsum = 0.f;
-        bf16x8 pf[4];
-#pragma unroll
-        for (int sk = 0; sk < 2; ++sk)
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                bf16x8 pk;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[sk][8 * a + e], c, -mc));
-                    lsum += p;
-                    pk[e] = (__bf16)p;
-                }
-                pf[2 * sk + a] = pk;
+            for (int e = 0; e < 8; ++e) {
+                const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[e], c, -mc));
+                const float b2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 + e], c, -mc));
+                lsum += a + b2;
+                p0[e] = (__bf16)a;
+                p1[e] = (__bf16)b2;
             }
-        l_run += lsum;
+            l_run += lsum;
+        };
 
-        // ---- O^T += V^T P^T
-        __builtin_amdgcn_sched_barrier(0);
+        // Order wanted inside an overlapped region: one MFMA, then a share of the vector work
+        // (a wavefront issues in order, so vector instructions placed behind a dependent MFMA
+        // would wait for it), then a share of the LDS fragment reads of the next region.
+        auto interleave = [&]() {
 #pragma unroll
-        for (int g0 = 0; g0 < kNV; g0 += kGroup) {
-            if (g0 + kGroup < kNV) {
-#pragma unroll
-                for (int i = 0; i < kGroup; ++i) vf[g0 + kGroup + i] = v_frag(g0 + kGroup + i);
+            for (int i = 0; i < kKSteps; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x402, 56 / kKSteps, 0);         // VALU + transcendental
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * kDTiles * 2 / kKSteps, 0);   // DS reads
             }
+        };
+
+        f32x16 s0, s1;
+        bf16x8 pf[4];
+
+        // ---- R0: S0^T = K0 Q^T (keys 0..31 of the tile)
+        {
+            bf16x8 kf[kKSteps];
+#pragma unroll
+            for (int i = 0; i < kKSteps; ++i) kf[i] = k_frag(0, i);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = g0; i < g0 + kGroup; ++i)
-                oacc[i / 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], pf[i % 4], oacc[i / 4], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 16; ++r) s0[r] = 0.f;
+#pragma unroll
+            for (int i = 0; i < kKSteps; ++i) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i], s0, 0, 0, 0);
         }
+        bf16x8 kf1[kKSteps];
+#pragma unroll
+        for (int i = 0; i < kKSteps; ++i) kf1[i] = k_frag(1, i);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- B0: row maximum of the first half; move the reference only past 2^8
+        {
+            const float mx = half_max(s0, 0);
+            if (__ballot((mx - m_run) * c > 8.0f) != 0) {
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+                m_run = m_new;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- R1: S1^T = K1 Q^T on the matrix pipe  ||  exponentials of the first half
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s1[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < kKSteps; ++i) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1[i], qf[i], s1, 0, 0, 0);
+        half_exp(s0, pf[0], pf[1]);
+        bf16x8 vf[kDTiles][2];
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = v_frag(dt, ks);
+        // keep the exponentials in this region (the optimiser would sink them to their first use)
+        asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(l_run));
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- B1: row maximum of the second half (the first half's P is still outside oacc)
+        {
+            const float mx = half_max(s1, 1);
+            if (__ballot((mx - m_run) * c > 8.0f) != 0) {
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pf[ks][e] = (__bf16)((float)pf[ks][e] * alpha);
+                m_run = m_new;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- R2: O^T += V0^T P0^T on the matrix pipe  ||  exponentials of the second half
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf[ks], oacc[dt], 0, 0, 0);
+        half_exp(s1, pf[2], pf[3]);
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = v_frag(dt, 2 + ks);
+        asm volatile("" : "+v"(pf[2]), "+v"(pf[3]), "+v"(l_run));
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- R3: O^T += V1^T P1^T
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf[2 + ks], oacc[dt], 0, 0, 0);
     };
 
     // ---- main sweep over the key tiles

@@ -4,7 +4,8 @@
 // Work split.  One workgroup owns kAttnBlockRows consecutive query positions of one
 // (sequence, query head); each of its wavefronts owns 32 of them.  Keys/values stream
 // through LDS in tiles of 64 positions, double buffered, loaded with 16-byte accesses one
-// tile ahead of the arithmetic.  Two workgroups share a compute unit, so each SIMD holds two
+// tile ahead of the arithmetic and written by the load unit itself (global_load ... lds), so
+// they never pass through registers.  Two workgroups share a compute unit, so each SIMD holds two
 // free-running wavefronts: one can feed the matrix pipe while the other does softmax.
 //
 // MFMA mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts).  The kernel computes the
@@ -30,14 +31,21 @@ namespace {
 
 constexpr int kBN = 64;                    // key positions per LDS tile
 
+// LDS image of one K or V tile: 64 rows of D bf16, NO padding (the direct global->LDS loads
+// fill 1 KiB of consecutive LDS per wavefront instruction).  Bank conflicts are avoided by an
+// XOR swizzle of the 16-byte chunk index inside a row instead:
+//   K: chunk ^ (row & 15)        -> the 16 rows a b128 fragment read touches hit 16 bank groups
+//   V: chunk ^ ((row & 3) << 2)  -> the 4 rows x 64 B a transposing read touches tile the banks
+// (for D = 64 a row has 8 chunks and the masks shrink to 7 and (row & 1) << 2).
 template <int D>
 struct Tile {
-    static constexpr int kKStride = D + 8;         // bf16 elements per K row (+16 B: conflict-free b128 reads)
-    static constexpr int kVStride = D + 32;        // bf16 elements per V row (+64 B: 4 rows x 64 B tile the banks)
-    static constexpr int kKElems = kBN * kKStride;
-    static constexpr int kVElems = kBN * kVStride;
-    static constexpr int kStageElems = kKElems + kVElems;
-    static constexpr size_t kLdsBytes = 2 * (size_t)kStageElems * sizeof(uint16_t);
+    static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kMatBytes = kBN * kRowBytes;           // one K or V tile
+    static constexpr int kStageBytes = 2 * kMatBytes;           // K then V
+    static constexpr size_t kLdsBytes = 2 * (size_t)kStageBytes;
+    __device__ static constexpr int k_swz(int row) { return row & (kChunks - 1); }
+    __device__ static constexpr int v_swz(int row) { return ((row & 3) << 2) & (kChunks - 1); }
 };
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -57,7 +65,7 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 // Transposing LDS read (ds_read_b64_tr_b16).  Inside every group of 16 lanes, lane j receives
 // element (j & 3) of the 8-byte words addressed by lanes (j >> 2), 4 + (j >> 2), 8 + (j >> 2)
 // and 12 + (j >> 2), in this order.
-__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p) {
+__device__ __forceinline__ s16x4 lds_read_tr(const char* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
@@ -97,12 +105,13 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
     constexpr int kBM = NW * 32;
     constexpr int kKSteps = D / 16;                  // MFMA k-steps over the head dimension
     constexpr int kDTiles = D / 32;                  // 32-row tiles of O^T
-    constexpr int kChunks = D / 8;                   // 16-byte chunks per K/V row
-    constexpr int kItemsMat = kChunks * (kBN / 4);   // (chunk, 4-key group) load items per matrix and tile
-    constexpr int kItems = 2 * kItemsMat;            // K items first, then V items
-    constexpr int kItemsPerThread = (kItems + kNT - 1) / kNT;
+    constexpr int kRowsPerInstr = 1024 / T::kRowBytes;          // rows one 64-lane x 16 B LDS-direct load fills
+    constexpr int kInstrPerMat = kBN / kRowsPerInstr;
+    constexpr int kInstrPerWave = kInstrPerMat / NW;
+    static_assert(kInstrPerMat % NW == 0, "tile rows must split evenly over the wavefronts");
+    constexpr int kLine = 256 / T::kRowBytes;                   // rows per 256-byte bank line (1 or 2)
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -146,42 +155,43 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
     const int qlo = q_base + 32 * wave;           // first query position of this wavefront
     const int qrow = qlo + li;                    // this lane's query position
 
-    // ---- K/V tile movement: global -> registers (one tile ahead) -> LDS, 16 bytes per access
-    u32x4 kvreg[kItemsPerThread][4];
-    const size_t tok_stride = (size_t)n_kv_heads * D;
-    const size_t head_off = ((size_t)row0 * n_kv_heads + kvh) * D;
-
-    auto load_tile = [&](int t) {
+    // ---- K/V tile movement: global -> LDS directly (no registers), 16 bytes per lane, one tile
+    // ahead.  Instruction i of this wavefront fills LDS rows (wave*kInstrPerWave + i)*kRowsPerInstr ..
+    // with lane l writing physical chunk l % kChunks of row l / kChunks; the lane therefore
+    // fetches the logical chunk that the swizzle stores there.
+    const size_t tok_bytes = (size_t)n_kv_heads * D * 2;
+    const char* k_head = (const char*)k + ((size_t)row0 * n_kv_heads + kvh) * D * 2;
+    const char* v_head = (const char*)v + ((size_t)row0 * n_kv_heads + kvh) * D * 2;
+    const int l_row = lane / T::kChunks, l_chunk = lane % T::kChunks;
+    uint32_t k_goff[kInstrPerWave], v_goff[kInstrPerWave];
 #pragma unroll
-        for (int it = 0; it < kItemsPerThread; ++it) {
-            const int item = tid + it * kNT;
-            if (kItems % kNT == 0 || item < kItems) {
-                const uint16_t* base = (item < kItemsMat ? k : v) + head_off;
-                const int im = item % kItemsMat;
-                const int dc = im % kChunks, kq = im / kChunks;
+    for (int i = 0; i < kInstrPerWave; ++i) {
+        const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
+        k_goff[i] = (uint32_t)(r * tok_bytes) + ((l_chunk ^ ((r / kLine) & (T::kChunks - 1))) << 4);
+        v_goff[i] = (uint32_t)(r * tok_bytes) + ((l_chunk ^ (((r / kLine) & (T::kChunks / 4 - 1)) << 2)) << 4);
+    }
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    auto load_tile = [&](int t, int stage) {
+        char* lds_k = smem + stage * T::kStageBytes + (wave * kInstrPerWave) * 1024;
+        char* lds_v = lds_k + T::kMatBytes;
+        const char* kt = k_head + (size_t)t * kBN * tok_bytes;
+        const char* vt = v_head + (size_t)t * kBN * tok_bytes;
+        const bool partial = (t + 1) * kBN > S;     // last tile of a ragged sequence: rows past the end re-read row S-1
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int key = min(t * kBN + 4 * kq + e, S - 1);
-                    kvreg[it][e] = *(const u32x4*)(base + key * tok_stride + dc * 8);
-                }
+        for (int i = 0; i < kInstrPerWave; ++i) {
+            // (opaque copies: otherwise every per-tile address is hoisted out of the sweep and
+            // the 64-bit pointers of all loads sit in registers for the whole kernel)
+            uint32_t kg = k_goff[i], vg = v_goff[i];
+            asm volatile("" : "+v"(kg), "+v"(vg));
+            if (partial) {
+                const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
+                const uint32_t back = (uint32_t)max(t * kBN + r - (S - 1), 0) * (uint32_t)tok_bytes;
+                kg -= back;
+                vg -= back;
             }
-        }
-    };
-    auto store_tile = [&](int stage) {
-        uint16_t* Ks = smem + stage * T::kStageElems;
-        uint16_t* Vs = Ks + T::kKElems;
-#pragma unroll
-        for (int it = 0; it < kItemsPerThread; ++it) {
-            const int item = tid + it * kNT;
-            if (kItems % kNT == 0 || item < kItems) {
-                const bool is_k = item < kItemsMat;
-                const int im = item % kItemsMat;
-                const int dc = im % kChunks, kq = im / kChunks;
-                uint16_t* dst = is_k ? Ks + 4 * kq * T::kKStride : Vs + 4 * kq * T::kVStride;
-                const int stride = is_k ? T::kKStride : T::kVStride;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) *(u32x4*)(dst + e * stride + dc * 8) = kvreg[it][e];
-            }
+            __builtin_amdgcn_global_load_lds((gptr_t)(kt + kg), (lptr_t)(lds_k + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(vt + vg), (lptr_t)(lds_v + i * 1024), 16, 0, 0);
         }
     };
 
@@ -193,12 +203,11 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
     }
-    load_tile(0);
+    load_tile(0, 0);
     // The fragments must have landed before the sweep starts: a load still pending at the loop
     // head would make every iteration wait for ALL outstanding loads, the prefetch included.
 #pragma unroll
     for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
-    store_tile(0);
 
     f32x16 oacc[kDTiles];
 #pragma unroll
@@ -209,26 +218,36 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
 
     // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
     const int krow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
-    const int k_lane_off = krow * T::kKStride + 8 * gl;
-    // V fragment addressing for the transposing read: this lane supplies the 8-byte word at
-    // key (8*gl + ((lane & 15) >> 2)) (+4 for the second read), head-dim column
-    // 16*((lane >> 4) & 1) + 4*(lane & 3) of the 16-key step / 32-column tile being fetched.
-    const int v_lane_off = (8 * gl + ((lane & 15) >> 2)) * T::kVStride + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    // Byte offset of this lane's K fragment inside a 32-row half: row krow, logical chunk
+    // 2*ks + gl, physical chunk (2*ks + gl) ^ swz.  XOR is bitwise, so the offset for k-step ks
+    // is k_lane ^ (ks << 5): one per-lane constant instead of one register per k-step.
+    const int k_lane = krow * T::kRowBytes + ((gl ^ ((krow / kLine) & (T::kChunks - 1))) << 4);
+    // V fragments come through the transposing read: this lane supplies the 8-byte word at key
+    // 8*gl + ((lane & 15) >> 2) (+4 for the second read) of the 16-key step, head-dim columns
+    // 32*dt + 16*((lane >> 4) & 1) + 4*(lane & 3) ..+3, i.e. half (lane & 1) of logical chunk
+    // 4*dt + 2*((lane >> 4) & 1) + ((lane & 3) >> 1); the swizzle only touches chunk bits 2..3,
+    // so the offset for tile dt is v_lane ^ (dt << 6).
+    const int vrow = 8 * gl + ((lane & 15) >> 2);
+    const int v_lane = vrow * T::kRowBytes +
+                       (((((vrow / kLine) & (T::kChunks / 4 - 1)) << 2) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) +
+                       8 * (lane & 1);
 
     // One 64-key tile.  The two 32-key halves are two independent instruction streams that
     // are overlapped inside the wavefront: while the matrix pipe runs QK^T of the second half
     // the vector pipe exponentiates the first, and while it runs P V of the first half the
     // vector pipe exponentiates the second.
     auto compute_tile = [&](int t, int stage) {
-        const uint16_t* Ks = smem + stage * T::kStageElems + k_lane_off;
-        const uint16_t* Vs = smem + stage * T::kStageElems + T::kKElems + v_lane_off;
+        const char* Ks = smem + stage * T::kStageBytes;
+        const char* Vs = Ks + T::kMatBytes;
         const int key0 = t * kBN;
+        int kl = k_lane, vl = v_lane;                    // opaque per tile, see load_tile
+        asm volatile("" : "+v"(kl), "+v"(vl));
 
-        auto k_frag = [&](int half, int ks) { return *(const bf16x8*)(Ks + (32 * half) * T::kKStride + 16 * ks); };
+        auto k_frag = [&](int half, int ks) { return *(const bf16x8*)(Ks + 32 * half * T::kRowBytes + (kl ^ (ks << 5))); };
         auto v_frag = [&](int dt, int ks) {
-            const uint16_t* p = Vs + (16 * ks) * T::kVStride + 32 * dt;
+            const char* p = Vs + 16 * ks * T::kRowBytes + (vl ^ (dt << 6));
             const s16x4 lo = lds_read_tr(p);
-            const s16x4 hi = lds_read_tr(p + 4 * T::kVStride);
+            const s16x4 hi = lds_read_tr(p + 4 * T::kRowBytes);
             return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         };
         // row maximum of one half (own 16 keys and the 16 of lane^32), masked on diagonal tiles
@@ -372,12 +391,11 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
 
     // ---- main sweep over the key tiles
     for (int t = 0; t < n_kv_tiles; ++t) {
-        __syncthreads();
-        const bool more = t + 1 < n_kv_tiles;
-        if (more) load_tile(t + 1);
+        __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0): this wavefront's share of tile t is in LDS
+        __syncthreads();                          // everyone's share is; everyone left the other stage
+        if (t + 1 < n_kv_tiles) load_tile(t + 1, (t + 1) & 1);
         // the wavefront takes part while some key of the tile is visible to its last row
         if (t * kBN <= qlo + 31) compute_tile(t, t & 1);
-        if (more) store_tile((t + 1) & 1);
     }
 
     // ---- epilogue: normalise, round to bf16, store; log2 of the denominator for the score pass

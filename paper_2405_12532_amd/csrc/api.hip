@@ -12,7 +12,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct BatchInfo {
     int32_t uniform_len;    // common length if all sequences have one (> 0), else 0
     int32_t max_len;
-    int64_t q_tiles;        // sum over sequences of ceil(S_b / kAttnBlockRows)
+    int64_t q_tiles;        // attention work items per head: sum over sequences of ceil(ceil(S_b / kAttnBlockRows) / 2)
 };
 
 int check_shape(const pyr_shape* s) {
@@ -38,7 +38,7 @@ int check_offsets(const int32_t* off, int32_t n_seqs, int32_t total, int32_t max
         const int32_t len = off[b + 1] - off[b];
         if (len > max_len) max_len = len;
         if (len != first) uniform = false;
-        tiles += (len + pyr::kAttnBlockRows - 1) / pyr::kAttnBlockRows;
+        tiles += ((len + pyr::kAttnBlockRows - 1) / pyr::kAttnBlockRows + 1) / 2;
     }
     if (off[n_seqs] != total) return PYR_ERR_OFFSETS;
     if (max_len_claimed >= 0 && max_len > max_len_claimed) return PYR_ERR_SHAPE;

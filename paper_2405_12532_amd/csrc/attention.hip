@@ -1,12 +1,19 @@
 // Causal softmax attention over packed, ragged sequences (Algorithm 1, "compute attention
 // weights of KV", applied to V), flash style: the S x S weight matrix never exists.
 //
-// Work split.  One workgroup owns kAttnBlockRows consecutive query positions of one
-// (sequence, query head); each of its wavefronts owns 32 of them.  Keys/values stream
-// through LDS in tiles of 64 positions, double buffered, loaded with 16-byte accesses one
-// tile ahead of the arithmetic and written by the load unit itself (global_load ... lds), so
-// they never pass through registers.  Two workgroups share a compute unit, so each SIMD holds two
-// free-running wavefronts: one can feed the matrix pipe while the other does softmax.
+// Work split.  The unit of work is a SEGMENT: kAttnBlockRows (128) consecutive query
+// positions of one (sequence, query head); each of the 4 wavefronts of a workgroup owns 32 of
+// them.  Segments are paired into ITEMS - query tile j of a sequence together with tile
+// n-1-j - so every item of a sequence sweeps the same number of causal key tiles.  Workgroups
+// are persistent: two per compute unit, each walking items with a fixed stride, and the first
+// K/V tile and the query fragments of the next segment are requested while the last tile of
+// the current one is still being computed, so a compute unit never drains between segments.
+// Two workgroups per compute unit put two free-running wavefronts on each SIMD: one feeds the
+// matrix pipe while the other does softmax arithmetic.
+//
+// Keys/values stream through LDS in tiles of 64 positions, double buffered, one tile ahead
+// of the arithmetic and written by the load unit itself (global_load ... lds), so they never
+// pass through registers.
 //
 // MFMA mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts).  The kernel computes the
 // TRANSPOSED logits  S^T = K Q^T  (keys x queries): in the accumulator layout a lane then
@@ -24,19 +31,25 @@
 // of the exponent is only moved (and the output rescaled) when some row's maximum grows by
 // more than 2^8 over it: probabilities then stay below 2^8, exact in fp32 and as precise in
 // bf16 as any other magnitude, and almost every tile skips the rescale.
+#include <type_traits>
+
 #include "pyr_internal.h"
 
 namespace pyr {
 namespace {
 
 constexpr int kBN = 64;                    // key positions per LDS tile
+constexpr int kNW = 4;                     // wavefronts per workgroup
+constexpr int kBM = kNW * 32;              // query positions per segment
+static_assert(kBM == kAttnBlockRows, "the host counts items with this segment height");
 
 // LDS image of one K or V tile: 64 rows of D bf16, NO padding (the direct global->LDS loads
 // fill 1 KiB of consecutive LDS per wavefront instruction).  Bank conflicts are avoided by an
 // XOR swizzle of the 16-byte chunk index inside a row instead:
 //   K: chunk ^ (row & 15)        -> the 16 rows a b128 fragment read touches hit 16 bank groups
 //   V: chunk ^ ((row & 3) << 2)  -> the 4 rows x 64 B a transposing read touches tile the banks
-// (for D = 64 a row has 8 chunks and the masks shrink to 7 and (row & 1) << 2).
+// (for D = 64 two rows share a 256-byte bank line: row is replaced by row / 2 and the masks
+// shrink to 7 and 1).
 template <int D>
 struct Tile {
     static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
@@ -44,12 +57,11 @@ struct Tile {
     static constexpr int kMatBytes = kBN * kRowBytes;           // one K or V tile
     static constexpr int kStageBytes = 2 * kMatBytes;           // K then V
     static constexpr size_t kLdsBytes = 2 * (size_t)kStageBytes;
-    __device__ static constexpr int k_swz(int row) { return row & (kChunks - 1); }
-    __device__ static constexpr int v_swz(int row) { return ((row & 3) << 2) & (kChunks - 1); }
 };
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) char* lptr_t;
 
 // v_permlane32_swap(x, x): result 0 holds lanes 0..31 of x in both halves, result 1 holds
 // lanes 32..63 of x in both halves; combining the two gives "own op other half" in every lane.
@@ -69,15 +81,31 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
 
-// prefix sums of the number of query tiles per sequence (ragged batches only)
-__global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
-                                                        int32_t block_rows, int32_t* __restrict__ tile_map) {
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at
+// lds + 16*l (lds wave-uniform), its source is base (wave-uniform) + voff (per lane).
+// Written in assembly on purpose: the compiler makes every later LDS read wait for ALL
+// outstanding loads of this kind (it cannot tell the two LDS stages apart), which would
+// serialise the prefetch of the next tile with the arithmetic on the current one.  The
+// kernel orders these loads itself: s_waitcnt vmcnt(0) and a barrier before a stage is read.
+__device__ __forceinline__ void lds_dma16(const char* base, uint32_t voff, char* lds) {
+    const uint32_t m0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(m0), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+__device__ __forceinline__ int items_of(int seq_len) {       // paired query tiles of one (sequence, head)
+    return ((seq_len + kBM - 1) / kBM + 1) / 2;
+}
+
+// prefix sums of the number of items per (sequence, head) (ragged batches only)
+__global__ __launch_bounds__(1024) void item_map_kernel(const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
+                                                        int32_t* __restrict__ item_map) {
     __shared__ int part[1024];
     const int tid = threadIdx.x;
     const int chunk = (n_seqs + 1023) / 1024;
     const int lo = min(tid * chunk, n_seqs), hi = min(lo + chunk, n_seqs);
     int sum = 0;
-    for (int b = lo; b < hi; ++b) sum += (seq_offsets[b + 1] - seq_offsets[b] + block_rows - 1) / block_rows;
+    for (int b = lo; b < hi; ++b) sum += items_of(seq_offsets[b + 1] - seq_offsets[b]);
     part[tid] = sum;
     __syncthreads();
     for (int d = 1; d < 1024; d <<= 1) {
@@ -88,27 +116,32 @@ __global__ __launch_bounds__(1024) void tile_map_kernel(const int32_t* __restric
     }
     int run = part[tid] - sum;
     for (int b = lo; b < hi; ++b) {
-        tile_map[b] = run;
-        run += (seq_offsets[b + 1] - seq_offsets[b] + block_rows - 1) / block_rows;
+        item_map[b] = run;
+        run += items_of(seq_offsets[b + 1] - seq_offsets[b]);
     }
-    if (tid == 1023) tile_map[n_seqs] = part[1023];
+    if (tid == 1023) item_map[n_seqs] = part[1023];
 }
 
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
+struct Segment {                // all fields wave-uniform
+    int row0;                   // first packed row of the sequence
+    int S;                      // its length
+    int h, kvh;                 // query head, key/value head
+    int q_base;                 // first query position of the segment
+};
+
+template <int D>
+__global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ tile_map,
-    int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds, float c,
-    uint16_t* __restrict__ out, float* __restrict__ lse) {
+    const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ item_map,
+    int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds,
+    long long items_per_xcd, float c, uint16_t* __restrict__ out, float* __restrict__ lse) {
     using T = Tile<D>;
-    constexpr int kNT = NW * 64;
-    constexpr int kBM = NW * 32;
-    constexpr int kKSteps = D / 16;                  // MFMA k-steps over the head dimension
-    constexpr int kDTiles = D / 32;                  // 32-row tiles of O^T
+    constexpr int kKSteps = D / 16;               // MFMA k-steps over the head dimension
+    constexpr int kDTiles = D / 32;               // 32-row tiles of O^T
     constexpr int kRowsPerInstr = 1024 / T::kRowBytes;          // rows one 64-lane x 16 B LDS-direct load fills
     constexpr int kInstrPerMat = kBN / kRowsPerInstr;
-    constexpr int kInstrPerWave = kInstrPerMat / NW;
-    static_assert(kInstrPerMat % NW == 0, "tile rows must split evenly over the wavefronts");
+    constexpr int kInstrPerWave = kInstrPerMat / kNW;
+    static_assert(kInstrPerMat % kNW == 0, "tile rows must split evenly over the wavefronts");
     constexpr int kLine = 256 / T::kRowBytes;                   // rows per 256-byte bank line (1 or 2)
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -117,104 +150,107 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31;                     // row (A operand) / column (B, C) inside a 32-wide tile
     const int gl = lane >> 5;                     // which half of the k-slots / accumulator rows
-
-    // ---- which (sequence, head, query tile).  Consecutive workgroup ids go to different XCDs
-    // (round robin), so the id is first split into (xcd, slot) and all query tiles and all
-    // query heads of one KV head are given to one XCD, heavy (late) tiles first: concurrently
-    // running workgroups of an XCD then read the same K/V rows through its L2.
     const int group = n_q_heads / n_kv_heads;
+
+    // ---- item -> segments.  Consecutive workgroup ids sit on different XCDs (round robin), so
+    // the id is split into (xcd, slot); the items of one XCD are ordered sequence, KV head,
+    // tile pair, query head of the group: workgroups that run at the same time on an XCD read
+    // the same K/V rows through its L2.
     const int xcd = blockIdx.x % xcds;
-    const long long slot = blockIdx.x / xcds;
-    const long long per_tile = (long long)(n_kv_heads / xcds) * group;
-    int b, n_tiles_b, tiles_before;
-    if (uniform_len > 0) {
-        n_tiles_b = (uniform_len + kBM - 1) / kBM;
-        b = (int)(slot / (per_tile * n_tiles_b));
-        tiles_before = b * n_tiles_b;
-    } else {
-        int lo = 0, hi = n_seqs;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (per_tile * tile_map[mid] <= slot) lo = mid; else hi = mid;
+    const long long slot_stride = gridDim.x / xcds;
+    const long long per_item = (long long)(n_kv_heads / xcds) * group;
+    long long item = blockIdx.x / xcds;           // index inside this XCD's list
+    int phase = 0;                                // 0: the late (long) tile of the pair, 1: the early one
+    int it_pair = 0, it_nq = 0;                   // decoded item (uniform)
+    Segment seg;
+
+    // decode `item`/`phase` into sg; returns false when the list is exhausted
+    auto decode = [&](Segment& sg) -> bool {
+        if (item >= items_per_xcd) return false;
+        if (phase == 0) {
+            long long before;
+            int b, n_items;
+            if (uniform_len > 0) {
+                n_items = items_of(uniform_len);
+                b = (int)(item / (per_item * n_items));
+                before = (long long)b * n_items;
+            } else {
+                int lo = 0, hi = n_seqs;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (per_item * item_map[mid] <= item) lo = mid; else hi = mid;
+                }
+                b = lo;
+                before = item_map[lo];
+                n_items = item_map[lo + 1] - item_map[lo];
+            }
+            const long long rem = item - per_item * before;
+            const int kv_local = (int)(rem / ((long long)n_items * group));
+            const int rem2 = (int)(rem % ((long long)n_items * group));
+            it_pair = rem2 / group;
+            sg.kvh = kv_local * xcds + xcd;
+            sg.h = sg.kvh * group + rem2 % group;
+            sg.row0 = uniform_len > 0 ? b * uniform_len : seq_offsets[b];
+            sg.S = uniform_len > 0 ? uniform_len : seq_offsets[b + 1] - sg.row0;
+            it_nq = (sg.S + kBM - 1) / kBM;
+            sg.q_base = (it_nq - 1 - it_pair) * kBM;
+        } else {
+            sg.q_base = it_pair * kBM;            // same sequence and head, the early tile
         }
-        b = lo;
-        tiles_before = tile_map[b];
-        n_tiles_b = tile_map[b + 1] - tiles_before;
-    }
-    const long long rem = slot - per_tile * tiles_before;
-    const int kv_local = (int)(rem / ((long long)n_tiles_b * group));
-    const int rem2 = (int)(rem % ((long long)n_tiles_b * group));
-    const int q_tile = n_tiles_b - 1 - rem2 / group;
-    const int kvh = kv_local * xcds + xcd;
-    const int h = kvh * group + rem2 % group;
+        return true;
+    };
+    // step to the next segment of the list
+    auto advance = [&]() {
+        if (phase == 0 && it_nq - 1 - it_pair != it_pair) {
+            phase = 1;
+        } else {
+            phase = 0;
+            item += slot_stride;
+        }
+    };
 
-    const int row0 = seq_offsets[b];
-    const int S = seq_offsets[b + 1] - row0;
-    const int q_base = q_tile * kBM;
-    const int n_kv_tiles = (min(S, q_base + kBM) + kBN - 1) / kBN;
-    const int qlo = q_base + 32 * wave;           // first query position of this wavefront
-    const int qrow = qlo + li;                    // this lane's query position
-
-    // ---- K/V tile movement: global -> LDS directly (no registers), 16 bytes per lane, one tile
-    // ahead.  Instruction i of this wavefront fills LDS rows (wave*kInstrPerWave + i)*kRowsPerInstr ..
+    // ---- per-lane constants of the data movement
+    // K/V tiles: instruction i of this wavefront fills LDS rows (wave*kInstrPerWave + i)*kRowsPerInstr ..
     // with lane l writing physical chunk l % kChunks of row l / kChunks; the lane therefore
     // fetches the logical chunk that the swizzle stores there.
-    const size_t tok_bytes = (size_t)n_kv_heads * D * 2;
-    const char* k_head = (const char*)k + ((size_t)row0 * n_kv_heads + kvh) * D * 2;
-    const char* v_head = (const char*)v + ((size_t)row0 * n_kv_heads + kvh) * D * 2;
+    const uint32_t tok_bytes = (uint32_t)n_kv_heads * D * 2;
     const int l_row = lane / T::kChunks, l_chunk = lane % T::kChunks;
     uint32_t k_goff[kInstrPerWave], v_goff[kInstrPerWave];
 #pragma unroll
     for (int i = 0; i < kInstrPerWave; ++i) {
         const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
-        k_goff[i] = (uint32_t)(r * tok_bytes) + ((l_chunk ^ ((r / kLine) & (T::kChunks - 1))) << 4);
-        v_goff[i] = (uint32_t)(r * tok_bytes) + ((l_chunk ^ (((r / kLine) & (T::kChunks / 4 - 1)) << 2)) << 4);
+        k_goff[i] = (uint32_t)r * tok_bytes + ((l_chunk ^ ((r / kLine) & (T::kChunks - 1))) << 4);
+        v_goff[i] = (uint32_t)r * tok_bytes + ((l_chunk ^ (((r / kLine) & (T::kChunks / 4 - 1)) << 2)) << 4);
     }
-    typedef const __attribute__((address_space(1))) void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
-    auto load_tile = [&](int t, int stage) {
+    auto load_tile = [&](const Segment& sg, int t, int stage) {
         char* lds_k = smem + stage * T::kStageBytes + (wave * kInstrPerWave) * 1024;
         char* lds_v = lds_k + T::kMatBytes;
-        const char* kt = k_head + (size_t)t * kBN * tok_bytes;
-        const char* vt = v_head + (size_t)t * kBN * tok_bytes;
-        const bool partial = (t + 1) * kBN > S;     // last tile of a ragged sequence: rows past the end re-read row S-1
+        const size_t first = ((size_t)(sg.row0 + t * kBN) * n_kv_heads + sg.kvh) * D * 2;
+        const char* kt = (const char*)k + first;
+        const char* vt = (const char*)v + first;
+        const bool partial = (t + 1) * kBN > sg.S;   // last tile of a ragged sequence: rows past the end re-read row S-1
 #pragma unroll
         for (int i = 0; i < kInstrPerWave; ++i) {
-            // (opaque copies: otherwise every per-tile address is hoisted out of the sweep and
-            // the 64-bit pointers of all loads sit in registers for the whole kernel)
             uint32_t kg = k_goff[i], vg = v_goff[i];
-            asm volatile("" : "+v"(kg), "+v"(vg));
             if (partial) {
                 const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
-                const uint32_t back = (uint32_t)max(t * kBN + r - (S - 1), 0) * (uint32_t)tok_bytes;
+                const uint32_t back = (uint32_t)max(t * kBN + r - (sg.S - 1), 0) * tok_bytes;
                 kg -= back;
                 vg -= back;
             }
-            __builtin_amdgcn_global_load_lds((gptr_t)(kt + kg), (lptr_t)(lds_k + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(vt + vg), (lptr_t)(lds_v + i * 1024), 16, 0, 0);
+            lds_dma16(kt, kg, lds_k + i * 1024);
+            lds_dma16(vt, vg, lds_v + i * 1024);
         }
     };
 
-    // ---- query fragments stay in registers for the whole sweep (B operand of S^T = K Q^T)
+    // query fragments: B operand of S^T = K Q^T, in registers for the whole segment
     bf16x8 qf[kKSteps];
-    {
-        const int row = min(qrow, S - 1);
-        const uint16_t* src = q + ((size_t)(row0 + row) * n_q_heads + h) * D + 8 * gl;
+    auto load_q = [&](const Segment& sg) {
+        const int row = min(sg.q_base + 32 * wave + li, sg.S - 1);
+        const uint16_t* src = q + ((size_t)(sg.row0 + row) * n_q_heads + sg.h) * D + 8 * gl;
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
-    }
-    load_tile(0, 0);
-    // The fragments must have landed before the sweep starts: a load still pending at the loop
-    // head would make every iteration wait for ALL outstanding loads, the prefetch included.
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
-
-    f32x16 oacc[kDTiles];
-#pragma unroll
-    for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    };
 
     // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
     const int krow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
@@ -232,16 +268,42 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
                        (((((vrow / kLine) & (T::kChunks / 4 - 1)) << 2) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) +
                        8 * (lane & 1);
 
+    // ---- state of the segment being computed
+    f32x16 oacc[kDTiles];
+    float m_run, l_run;
+    int qlo, qrow;                                // first query position of the wavefront / of this lane
+    auto reset_state = [&](const Segment& sg) {
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+        m_run = -INFINITY;
+        l_run = 0.f;
+        qlo = sg.q_base + 32 * wave;
+        qrow = qlo + li;
+    };
+
     // One 64-key tile.  The two 32-key halves are two independent instruction streams that
     // are overlapped inside the wavefront: while the matrix pipe runs QK^T of the second half
     // the vector pipe exponentiates the first, and while it runs P V of the first half the
-    // vector pipe exponentiates the second.
-    auto compute_tile = [&](int t, int stage) {
-        const char* Ks = smem + stage * T::kStageBytes;
-        const char* Vs = Ks + T::kMatBytes;
-        const int key0 = t * kBN;
-        int kl = k_lane, vl = v_lane;                    // opaque per tile, see load_tile
+    // vector pipe exponentiates the second.  The tile is written as two pieces, tile_front
+    // (up to the last use of the query fragments) and tile_back, so that the last tile of a
+    // segment can request the next segment's query fragments in between.
+    f32x16 s0, s1;
+    bf16x8 pf[4];
+    bf16x8 vf[kDTiles][2];
+    int kl, vl;
+    const char *Ks, *Vs;
+    int key0, S;
+    auto tile_begin = [&](const Segment& sg, int t, int stage) {
+        Ks = smem + stage * T::kStageBytes;
+        Vs = Ks + T::kMatBytes;
+        key0 = t * kBN;
+        S = sg.S;
+        kl = k_lane;                                     // opaque per tile, see load_tile
+        vl = v_lane;
         asm volatile("" : "+v"(kl), "+v"(vl));
+    };
 
         auto k_frag = [&](int half, int ks) { return *(const bf16x8*)(Ks + 32 * half * T::kRowBytes + (kl ^ (ks << 5))); };
         auto v_frag = [&](int dt, int ks) {
@@ -282,7 +344,6 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
             }
             l_run += lsum;
         };
-
         // Order wanted inside an overlapped region: one MFMA, then a share of the vector work
         // (a wavefront issues in order, so vector instructions placed behind a dependent MFMA
         // would wait for it), then a share of the LDS fragment reads of the next region.
@@ -294,10 +355,22 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 * kDTiles * 2 / kKSteps, 0);   // DS reads
             }
         };
+        // move the exponent reference only when some row outgrew it by more than 2^8
+        auto move_reference = [&](float mx, auto&& also) {
+            if (__ballot((mx - m_run) * c > 8.0f) != 0) {
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+                also(alpha);
+                m_run = m_new;
+            }
+        };
 
-        f32x16 s0, s1;
-        bf16x8 pf[4];
-
+    auto tile_front = [&]() {
         // ---- R0: S0^T = K0 Q^T (keys 0..31 of the tile)
         {
             bf16x8 kf[kKSteps];
@@ -314,20 +387,8 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
         for (int i = 0; i < kKSteps; ++i) kf1[i] = k_frag(1, i);
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- B0: row maximum of the first half; move the reference only past 2^8
-        {
-            const float mx = half_max(s0, 0);
-            if (__ballot((mx - m_run) * c > 8.0f) != 0) {
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                l_run *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-                m_run = m_new;
-            }
-        }
+        // ---- B0: row maximum of the first half
+        move_reference(half_max(s0, 0), [](float) {});
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- R1: S1^T = K1 Q^T on the matrix pipe  ||  exponentials of the first half
@@ -336,7 +397,6 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
 #pragma unroll
         for (int i = 0; i < kKSteps; ++i) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1[i], qf[i], s1, 0, 0, 0);
         half_exp(s0, pf[0], pf[1]);
-        bf16x8 vf[kDTiles][2];
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
@@ -345,25 +405,15 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
         asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(l_run));
         interleave();
         __builtin_amdgcn_sched_barrier(0);
-
+    };
+    auto tile_back = [&]() {
         // ---- B1: row maximum of the second half (the first half's P is still outside oacc)
-        {
-            const float mx = half_max(s1, 1);
-            if (__ballot((mx - m_run) * c > 8.0f) != 0) {
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                l_run *= alpha;
+        move_reference(half_max(s1, 1), [&](float alpha) {
 #pragma unroll
-                for (int dt = 0; dt < kDTiles; ++dt)
+            for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[ks][e] = (__bf16)((float)pf[ks][e] * alpha);
-                m_run = m_new;
-            }
-        }
+                for (int e = 0; e < 8; ++e) pf[ks][e] = (__bf16)((float)pf[ks][e] * alpha);
+        });
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- R2: O^T += V0^T P0^T on the matrix pipe  ||  exponentials of the second half
@@ -389,40 +439,90 @@ __global__ __launch_bounds__(NW * 64, 512 / (NW * 64)) void attention_kernel(
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf[2 + ks], oacc[dt], 0, 0, 0);
     };
 
-    // ---- main sweep over the key tiles
-    for (int t = 0; t < n_kv_tiles; ++t) {
-        __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0): this wavefront's share of tile t is in LDS
-        __syncthreads();                          // everyone's share is; everyone left the other stage
-        if (t + 1 < n_kv_tiles) load_tile(t + 1, (t + 1) & 1);
-        // the wavefront takes part while some key of the tile is visible to its last row
-        if (t * kBN <= qlo + 31) compute_tile(t, t & 1);
-    }
+    // normalise, round to bf16, store; log2 of the denominator for the score pass
+    auto epilogue = [&](const Segment& sg) {
+        const float ltot = sum_with_other_half(l_run);
+        const float inv = 1.0f / ltot;
+        if (qrow < sg.S) {
+            uint16_t* dst = out + ((size_t)(sg.row0 + qrow) * n_q_heads + sg.h) * D + 4 * gl;
+#pragma unroll
+            for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][4 * a + e] * inv);
+                    *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
+                }
+            if (lse != nullptr && gl == 0)
+                lse[(size_t)(sg.row0 + qrow) * n_q_heads + sg.h] = m_run * c + __builtin_amdgcn_logf(ltot);
+        }
+    };
 
-    // ---- epilogue: normalise, round to bf16, store; log2 of the denominator for the score pass
-    const float ltot = sum_with_other_half(l_run);
-    const float inv = 1.0f / ltot;
-    if (qrow < S) {
-        uint16_t* dst = out + ((size_t)(row0 + qrow) * n_q_heads + h) * D + 4 * gl;
+    // ---- the walk over this workgroup's segments
+    if (!decode(seg)) return;
+    int g = 0;                                    // tiles issued so far: LDS stage = g & 1
+    load_q(seg);
+    load_tile(seg, 0, 0);
+    while (true) {
+        // The query fragments must have landed before the sweep starts: a register load still
+        // pending at the head of the tile loop would make every iteration wait for ALL
+        // outstanding loads, the tile prefetch included.
 #pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                bf16x4 o4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][4 * a + e] * inv);
-                *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
+        for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
+        reset_state(seg);
+        const int n_kv_tiles = (min(seg.S, seg.q_base + kBM) + kBN - 1) / kBN;
+        for (int t = 0; t + 1 < n_kv_tiles; ++t, ++g) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's share of tile t is in LDS
+            __syncthreads();                      // everyone's share is; everyone left the other stage
+            load_tile(seg, t + 1, (g + 1) & 1);
+            // the wavefront takes part while some key of the tile is visible to its last row
+            if (t * kBN <= qlo + 31) {
+                tile_begin(seg, t, g & 1);
+                tile_front();
+                tile_back();
             }
-        if (lse != nullptr && gl == 0)
-            lse[(size_t)(row0 + qrow) * n_q_heads + h] = m_run * c + __builtin_amdgcn_logf(ltot);
+        }
+        // last tile of the segment: the other stage and the query registers go to the next
+        // segment (when the list is exhausted the same fragments are simply fetched again)
+        const int t_last = n_kv_tiles - 1;
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        __syncthreads();
+        advance();
+        Segment nxt = seg;
+        const bool have_next = decode(nxt);
+        if (have_next) load_tile(nxt, 0, (g + 1) & 1);
+        const bool takes_part = t_last * kBN <= qlo + 31;
+        if (takes_part) {
+            tile_begin(seg, t_last, g & 1);
+            tile_front();
+        }
+        load_q(nxt);
+        if (takes_part) tile_back();
+        ++g;
+        epilogue(seg);
+        if (!have_next) break;
+        seg = nxt;
     }
 }
 
-template <int D, int NW>
+int device_slots() {
+    static int slots = 0;            // workgroups the device holds at 2 per compute unit
+    if (slots == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        slots = 2 * cus;
+    }
+    return slots;
+}
+
+template <int D>
 int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
-                       const pyr_shape& s, int32_t uniform_len, int64_t total_q_tiles, float c,
-                       void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
-    static_assert(NW * 32 == kAttnBlockRows, "the host tile count assumes this block height");
-    auto kern = attention_kernel<D, NW>;
+                       const pyr_shape& s, int32_t uniform_len, int64_t total_items, float c,
+                       void* out, float* lse, int32_t* item_map, hipStream_t stream) {
+    auto kern = attention_kernel<D>;
     static bool attr_done = false;   // benign race: the attribute call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -430,31 +530,33 @@ int launch_attention_d(const void* q, const void* k, const void* v, const int32_
             return PYR_ERR_LAUNCH;
         attr_done = true;
     }
+    if (total_items == 0) return PYR_OK;
     if (uniform_len == 0) {
-        hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs,
-                           (int32_t)kAttnBlockRows, tile_map);
+        hipLaunchKernelGGL(item_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs, item_map);
         if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
     }
-    const int64_t n_blocks = total_q_tiles * s.n_q_heads;
-    if (n_blocks == 0) return PYR_OK;
     const int xcds = (s.n_kv_heads % 8 == 0) ? 8 : 1;
-    hipLaunchKernelGGL(kern, dim3((unsigned)n_blocks), dim3(NW * 64), Tile<D>::kLdsBytes, stream,
+    const long long items_per_xcd = (long long)total_items * s.n_q_heads / xcds;
+    long long per_xcd_slots = device_slots() / xcds;
+    if (per_xcd_slots > items_per_xcd) per_xcd_slots = items_per_xcd;
+    const unsigned grid = (unsigned)(per_xcd_slots * xcds);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), Tile<D>::kLdsBytes, stream,
                        (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, seq_offsets_dev,
-                       (const int32_t*)tile_map, s.n_seqs, s.n_q_heads, s.n_kv_heads, uniform_len, xcds, c,
-                       (uint16_t*)out, lse);
+                       (const int32_t*)item_map, s.n_seqs, s.n_q_heads, s.n_kv_heads, uniform_len, xcds,
+                       items_per_xcd, c, (uint16_t*)out, lse);
     return check_launch();
 }
 
 }  // namespace
 
 int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
-                     const pyr_shape& shape, int32_t uniform_len, int64_t total_q_tiles, float scale_log2,
-                     void* out, float* lse, int32_t* tile_map, hipStream_t stream) {
+                     const pyr_shape& shape, int32_t uniform_len, int64_t total_items, float scale_log2,
+                     void* out, float* lse, int32_t* item_map, hipStream_t stream) {
     if (shape.head_dim == 128)
-        return launch_attention_d<128, kAttnBlockRows / 32>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
-                                       out, lse, tile_map, stream);
-    return launch_attention_d<64, kAttnBlockRows / 32>(q, k, v, seq_offsets_dev, shape, uniform_len, total_q_tiles, scale_log2,
-                                  out, lse, tile_map, stream);
+        return launch_attention_d<128>(q, k, v, seq_offsets_dev, shape, uniform_len, total_items, scale_log2,
+                                       out, lse, item_map, stream);
+    return launch_attention_d<64>(q, k, v, seq_offsets_dev, shape, uniform_len, total_items, scale_log2,
+                                  out, lse, item_map, stream);
 }
 
 }  // namespace pyr

@@ -17,7 +17,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Rows of query positions one attention workgroup owns (the tile map counts these).
+// Query positions per attention segment; two segments (tiles j and n-1-j of a sequence) form one work item.
 constexpr int kAttnBlockRows = 128;
 
 // Every launcher returns PYR_OK or PYR_ERR_LAUNCH; arguments are already validated.
@@ -29,8 +29,8 @@ int launch_select(const float* scores, const int32_t* seq_offsets_dev, const int
                   hipStream_t stream);
 
 int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
-                     const pyr_shape& shape, int32_t uniform_len, int64_t total_q_tiles, float scale_log2,
-                     void* out, float* lse, int32_t* tile_map, hipStream_t stream);
+                     const pyr_shape& shape, int32_t uniform_len, int64_t total_items, float scale_log2,
+                     void* out, float* lse, int32_t* item_map, hipStream_t stream);
 
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
                  const pyr_shape& shape, int32_t w, float scale_log2, float* scores, hipStream_t stream);

@@ -27,10 +27,12 @@
 //
 // Numerics: bf16 products, fp32 accumulation, fp32 online softmax in base 2 with the scale
 // folded into one FMA per logit; probabilities are rounded to bf16 for the PV product while
-// the softmax denominator is summed from the unrounded fp32 values.  The running reference
-// of the exponent is only moved (and the output rescaled) when some row's maximum grows by
-// more than 2^8 over it: probabilities then stay below 2^8, exact in fp32 and as precise in
-// bf16 as any other magnitude, and almost every tile skips the rescale.
+// the softmax denominator is summed from the unrounded fp32 values.  The reference of the
+// exponent is NOT the running row maximum: it is set from the true maxima on the first tile
+// and afterwards only when some row's partial sum shows that it outgrew the reference by
+// more than 2^16 (probabilities stay exact in fp32 and as precise in bf16 as at any other
+// magnitude).  The common tile therefore takes no row maximum, no cross-lane exchange and no
+// rescale of the output: one FMA, one exponential, one add and half a convert per logit.
 #include <type_traits>
 
 #include "pyr_internal.h"
@@ -312,26 +314,21 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
             const s16x4 hi = lds_read_tr(p + 4 * T::kRowBytes);
             return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         };
-        // row maximum of one half (own 16 keys and the 16 of lane^32), masked on diagonal tiles
-        auto half_max = [&](f32x16& sv, int half) {
+        // causal / end-of-sequence mask of one half (diagonal tiles only; wave-uniform test)
+        auto mask_half = [&](f32x16& sv, int half) {
             const int kbase = key0 + 32 * half;
-            if ((kbase + 31 > qlo) || (kbase + 32 > S)) {            // wave-uniform
+            if ((kbase + 31 > qlo) || (kbase + 32 > S)) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int key = kbase + 16 * (r >> 3) + 8 * gl + (r & 7);
                     if (key > qrow || key >= S) sv[r] = -INFINITY;
                 }
             }
-            float mx = sv[0];
-#pragma unroll
-            for (int r = 1; r < 16; r += 2) {
-                const float nxt = r + 1 < 16 ? sv[r + 1] : sv[r];
-                mx = fmaxf(fmaxf(mx, sv[r]), nxt);                  // v_max3_f32
-            }
-            return max_with_other_half(mx);
         };
-        // p = 2^(c s - c m) for one half: fp32 row sum, bf16 fragments for the PV product
-        auto half_exp = [&](const f32x16& sv, bf16x8& p0, bf16x8& p1) {
+        // p = 2^(c s - c m) for one half against the CURRENT reference m: fp32 row sum of this
+        // lane's 16 keys, bf16 fragments for the PV product.  No row maximum is taken: a
+        // reference that has become too small shows up as a huge (or infinite, or NaN) sum.
+        auto half_exp = [&](const f32x16& sv, bf16x8& p0, bf16x8& p1) -> float {
             const float mc = m_run * c;
             float lsum = 0.f;
 #pragma unroll
@@ -342,7 +339,31 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
                 p0[e] = (__bf16)a;
                 p1[e] = (__bf16)b2;
             }
-            l_run += lsum;
+            return lsum;
+        };
+        // Rare path: some row of the wavefront outgrew the reference by more than 2^16 (always
+        // the case on the first tile, where the reference is -inf).  Take the true row maxima,
+        // move the reference, rescale what has been accumulated, redo the half.
+        auto renew_half = [&](const f32x16& sv, bf16x8& p0, bf16x8& p1, float lsum) -> float {
+            if (__ballot(!(lsum <= 65536.0f)) != 0) {
+                float mx = sv[0];
+#pragma unroll
+                for (int r = 1; r < 16; r += 2) {
+                    const float nxt = r + 1 < 16 ? sv[r + 1] : sv[r];
+                    mx = fmaxf(fmaxf(mx, sv[r]), nxt);              // v_max3_f32
+                }
+                mx = max_with_other_half(mx);
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+                m_run = m_new;
+                lsum = half_exp(sv, p0, p1);
+            }
+            return lsum;
         };
         // Order wanted inside an overlapped region: one MFMA, then a share of the vector work
         // (a wavefront issues in order, so vector instructions placed behind a dependent MFMA
@@ -353,20 +374,6 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x402, 56 / kKSteps, 0);         // VALU + transcendental
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 * kDTiles * 2 / kKSteps, 0);   // DS reads
-            }
-        };
-        // move the exponent reference only when some row outgrew it by more than 2^8
-        auto move_reference = [&](float mx, auto&& also) {
-            if (__ballot((mx - m_run) * c > 8.0f) != 0) {
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                l_run *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-                also(alpha);
-                m_run = m_new;
             }
         };
 
@@ -386,9 +393,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
 #pragma unroll
         for (int i = 0; i < kKSteps; ++i) kf1[i] = k_frag(1, i);
         __builtin_amdgcn_sched_barrier(0);
-
-        // ---- B0: row maximum of the first half
-        move_reference(half_max(s0, 0), [](float) {});
+        mask_half(s0, 0);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- R1: S1^T = K1 Q^T on the matrix pipe  ||  exponentials of the first half
@@ -396,39 +401,35 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         for (int r = 0; r < 16; ++r) s1[r] = 0.f;
 #pragma unroll
         for (int i = 0; i < kKSteps; ++i) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1[i], qf[i], s1, 0, 0, 0);
-        half_exp(s0, pf[0], pf[1]);
+        float ls = half_exp(s0, pf[0], pf[1]);
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = v_frag(dt, ks);
         // keep the exponentials in this region (the optimiser would sink them to their first use)
-        asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(l_run));
+        asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(ls));
         interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        l_run += renew_half(s0, pf[0], pf[1], ls);
+        mask_half(s1, 1);
         __builtin_amdgcn_sched_barrier(0);
     };
     auto tile_back = [&]() {
-        // ---- B1: row maximum of the second half (the first half's P is still outside oacc)
-        move_reference(half_max(s1, 1), [&](float alpha) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[ks][e] = (__bf16)((float)pf[ks][e] * alpha);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-
         // ---- R2: O^T += V0^T P0^T on the matrix pipe  ||  exponentials of the second half
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf[ks], oacc[dt], 0, 0, 0);
-        half_exp(s1, pf[2], pf[3]);
+        float ls = half_exp(s1, pf[2], pf[3]);
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = v_frag(dt, 2 + ks);
-        asm volatile("" : "+v"(pf[2]), "+v"(pf[3]), "+v"(l_run));
+        asm volatile("" : "+v"(pf[2]), "+v"(pf[3]), "+v"(ls));
         interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        l_run += renew_half(s1, pf[2], pf[3], ls);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- R3: O^T += V1^T P1^T

@@ -28,9 +28,13 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per attention launch at the default workload, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs scaled by a copy kernel of known size (profiles/attention_64x2k_pmc.txt).
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch at the default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script, scaled by what the same counters read for the hidden-row gather (a plain copy of known
+# size); the counter summary is profiles/layer_step_64x2k_pmc.txt.
+MEASURED_TRAFFIC = {
+    ("64x2k", "attention"): 8.06e9,       # 6.81 GB read + 1.25 GB written (algorithmic 4.31 GB)
+    ("64x2k", "gather"): 5.99e9,          # read = written = algorithmic after calibration
+}
 
 
 def attention_flops(seq_lens, n_q_heads, head_dim):

@@ -129,9 +129,21 @@ def _gen_sequence(wl: Workload, layer: int, b: int, u_kv: np.ndarray, want_hidde
         q += np.float32(wl.q_amp) * np.repeat(u_kv, g, axis=0)[None, :, :]
     res = {"q": f32_to_bf16_bits(q), "k": f32_to_bf16_bits(k), "v": f32_to_bf16_bits(v), "heavy": heavy}
     if want_hidden and wl.hidden_dim > 0:
-        h = _seq_rng(wl.seed, layer, b, 5).standard_normal((S, wl.hidden_dim), dtype=np.float32)
-        res["hidden"] = f32_to_bf16_bits(h)
+        res["hidden"] = _gen_hidden(wl, layer, b)
     return res
+
+
+def _gen_hidden(wl: Workload, layer: int, b: int):
+    h = _seq_rng(wl.seed, layer, b, 5).standard_normal((wl.seq_lens[b], wl.hidden_dim), dtype=np.float32)
+    return f32_to_bf16_bits(h)
+
+
+def make_hidden(wl: Workload, layer: int = 0, threads: int | None = None):
+    """The hidden rows of make_inputs alone (same values), [T, D] uint16 bf16 bit patterns."""
+    if threads is None:
+        threads = max(1, min(16, len(os.sched_getaffinity(0))))
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        return np.concatenate(list(ex.map(lambda b: _gen_hidden(wl, layer, b), range(wl.n_seqs))), axis=0)
 
 
 def make_inputs(wl: Workload, layer: int = 0, want_hidden: bool = True, threads: int | None = None):

@@ -1,19 +1,19 @@
 // Causal softmax attention over packed, ragged sequences (Algorithm 1, "compute attention
 // weights of KV", applied to V), flash style: the S x S weight matrix never exists.
 //
-// Work split.  The unit of work is a SEGMENT: kAttnBlockRows (128) consecutive query
-// positions of one (sequence, query head); each of the 4 wavefronts of a workgroup owns 32 of
+// Work split.  The unit of work is a SEGMENT: kAttnBlockRows (256) consecutive query
+// positions of one (sequence, query head); each of the 8 wavefronts of a workgroup owns 32 of
 // them.  Segments are paired into ITEMS - query tile j of a sequence together with tile
 // n-1-j - so every item of a sequence sweeps the same number of causal key tiles.  Workgroups
-// are persistent: two per compute unit, each walking items with a fixed stride, and the first
-// K/V tile and the query fragments of the next segment are requested while the last tile of
-// the current one is still being computed, so a compute unit never drains between segments.
-// Two workgroups per compute unit put two free-running wavefronts on each SIMD: one feeds the
-// matrix pipe while the other does softmax arithmetic.
+// are persistent, one per compute unit (two wavefronts per SIMD), each walking items with a
+// fixed stride.  The 32-row blocks are dealt to the wavefronts so that the two wavefronts of a
+// SIMD own blocks b and 7-b: every SIMD gets the same amount of causal work per segment.
 //
-// Keys/values stream through LDS in tiles of 64 positions, double buffered, one tile ahead
-// of the arithmetic and written by the load unit itself (global_load ... lds), so they never
-// pass through registers.
+// Keys/values stream through LDS in tiles of 64 positions in rings of three tiles each,
+// written by the load unit itself (global_load ... lds), so they never pass through
+// registers.  The tiles of all segments of a workgroup form ONE stream: the loads run three
+// (K) and one (V) stream positions ahead of the arithmetic, across segment boundaries, so
+// the compute unit never drains between segments.
 //
 // MFMA mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts).  The kernel computes the
 // TRANSPOSED logits  S^T = K Q^T  (keys x queries): in the accumulator layout a lane then
@@ -23,16 +23,28 @@
 // what the lane already holds once the K rows of a 32-key sub-tile are fed in the order
 // "bits 2 and 3 of the row number swapped".  V sits in LDS row-major like K; its A-operand
 // fragments (8 keys of one head-dim column per lane) come out of LDS already transposed
-// through ds_read_b64_tr_b16, so no transposition pass and no 2-byte LDS traffic exists.
+// through ds_read_b64_tr_b16.
+//
+// Software pipeline inside a wavefront.  A 64-key tile is two 32-key halves; per half there
+// is one group of MFMAs for the logits (QK) and one for the output (PV), and the
+// exponentials of a half are cut in two chunks (E..a, E..b).  In the steady state every
+// group of MFMAs is issued interleaved, instruction by instruction, with one chunk of
+// exponentials of ANOTHER half and with the LDS reads of the next group's fragments:
+//     QK0(t+1) | E1a(t)      PV0(t) | E1b(t)      QK1(t+1) | E0a(t+1)      PV1(t) | E0b(t+1)
+// A matrix instruction keeps the matrix pipe busy for 32 cycles but occupies the issue port
+// for about 10; the vector work of one slice (one FMA, one exponential, one add, half a
+// convert per logit pair) fits in the remainder, so one wavefront alone nearly saturates the
+// matrix pipe and the second wavefront of the SIMD covers what is left (barriers, waits).
+// Scheduling barriers after every slice pin this order.
 //
 // Numerics: bf16 products, fp32 accumulation, fp32 online softmax in base 2 with the scale
 // folded into one FMA per logit; probabilities are rounded to bf16 for the PV product while
 // the softmax denominator is summed from the unrounded fp32 values.  The reference of the
-// exponent is NOT the running row maximum: it is set from the true maxima on the first tile
-// and afterwards only when some row's partial sum shows that it outgrew the reference by
-// more than 2^16 (probabilities stay exact in fp32 and as precise in bf16 as at any other
-// magnitude).  The common tile therefore takes no row maximum, no cross-lane exchange and no
-// rescale of the output: one FMA, one exponential, one add and half a convert per logit.
+// exponent is NOT the running row maximum: it is set from the true maxima of the first 32
+// keys and afterwards only moved when some row's partial sum shows that it outgrew the
+// reference by more than 2^16 (probabilities stay exact in fp32 and as precise in bf16 as at
+// any other magnitude).  The common tile therefore takes no row maximum, no cross-lane
+// exchange and no rescale of the output.
 #include <type_traits>
 
 #include "pyr_internal.h"
@@ -41,8 +53,9 @@ namespace pyr {
 namespace {
 
 constexpr int kBN = 64;                    // key positions per LDS tile
-constexpr int kNW = 4;                     // wavefronts per workgroup
+constexpr int kNW = 8;                     // wavefronts per workgroup
 constexpr int kBM = kNW * 32;              // query positions per segment
+constexpr int kRing = 4;                   // LDS tiles per ring (one ring for K, one for V)
 static_assert(kBM == kAttnBlockRows, "the host counts items with this segment height");
 
 // LDS image of one K or V tile: 64 rows of D bf16, NO padding (the direct global->LDS loads
@@ -57,11 +70,11 @@ struct Tile {
     static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
     static constexpr int kRowBytes = D * 2;
     static constexpr int kMatBytes = kBN * kRowBytes;           // one K or V tile
-    static constexpr int kStageBytes = 2 * kMatBytes;           // K then V
-    static constexpr size_t kLdsBytes = 2 * (size_t)kStageBytes;
+    static constexpr size_t kLdsBytes = 2 * (size_t)kRing * kMatBytes;
 };
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) char* lptr_t;
 
@@ -79,20 +92,26 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 // Transposing LDS read (ds_read_b64_tr_b16).  Inside every group of 16 lanes, lane j receives
 // element (j & 3) of the 8-byte words addressed by lanes (j >> 2), 4 + (j >> 2), 8 + (j >> 2)
 // and 12 + (j >> 2), in this order.
-__device__ __forceinline__ s16x4 lds_read_tr(const char* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
+__device__ __forceinline__ s16x4 lds_read_tr(int lds_addr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(uintptr_t)lds_addr);
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane l's data lands at
 // lds + 16*l (lds wave-uniform), its source is base (wave-uniform) + voff (per lane).
-// Written in assembly on purpose: the compiler makes every later LDS read wait for ALL
-// outstanding loads of this kind (it cannot tell the two LDS stages apart), which would
-// serialise the prefetch of the next tile with the arithmetic on the current one.  The
-// kernel orders these loads itself: s_waitcnt vmcnt(0) and a barrier before a stage is read.
+// Written in assembly on purpose: the compiler would make every later LDS read wait for ALL
+// outstanding loads of this kind (it cannot tell the ring slots apart).  The kernel orders
+// these loads itself: s_waitcnt vmcnt(0) and a barrier before a slot is read.
 __device__ __forceinline__ void lds_dma16(const char* base, uint32_t voff, char* lds) {
     const uint32_t m0 = (uint32_t)(uintptr_t)(lptr_t)lds;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(m0), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // v_cvt_pk_bf16_f32
+    bf16x2 v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 __device__ __forceinline__ int items_of(int seq_len) {       // paired query tiles of one (sequence, head)
@@ -129,6 +148,17 @@ struct Segment {                // all fields wave-uniform
     int S;                      // its length
     int h, kvh;                 // query head, key/value head
     int q_base;                 // first query position of the segment
+    int n_tiles;                // key tiles the workgroup sweeps for it
+};
+
+// A position in the workgroup's list of segments (and, for the load cursors, in the stream
+// of key tiles).  All fields wave-uniform.
+struct Walker {
+    int item;                   // index inside this XCD's item list
+    int phase;                  // 0: the late (long) tile of the pair, 1: the early one
+    int pair, nq;               // decoded item: pair index, query tiles of the sequence
+    int t;                      // key tile inside the segment (load cursors only)
+    Segment seg;
 };
 
 template <int D>
@@ -136,20 +166,23 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ item_map,
     int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds,
-    long long items_per_xcd, float c, uint16_t* __restrict__ out, float* __restrict__ lse) {
+    int32_t items_per_xcd, float c, uint16_t* __restrict__ out, float* __restrict__ lse) {
     using T = Tile<D>;
-    constexpr int kKSteps = D / 16;               // MFMA k-steps over the head dimension
+    constexpr int NS = D / 16;                    // MFMAs per group = k-steps of QK^T = V fragments of a half
     constexpr int kDTiles = D / 32;               // 32-row tiles of O^T
+    constexpr int EPS = 8 / NS;                   // logits of a chunk handled per slice (1 or 2)
+    constexpr int kLook = NS - 2;                 // slices between the LDS read of a fragment and its MFMA
     constexpr int kRowsPerInstr = 1024 / T::kRowBytes;          // rows one 64-lane x 16 B LDS-direct load fills
     constexpr int kInstrPerMat = kBN / kRowsPerInstr;
     constexpr int kInstrPerWave = kInstrPerMat / kNW;
-    static_assert(kInstrPerMat % kNW == 0, "tile rows must split evenly over the wavefronts");
+    static_assert(kInstrPerMat % kNW == 0 && kInstrPerWave >= 1, "tile rows must split evenly over the wavefronts");
     constexpr int kLine = 256 / T::kRowBytes;                   // rows per 256-byte bank line (1 or 2)
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rb = wave < 4 ? wave : 11 - wave;   // 32-row block of this wavefront (SIMD s: blocks s and 7-s)
     const int li = lane & 31;                     // row (A operand) / column (B, C) inside a 32-wide tile
     const int gl = lane >> 5;                     // which half of the k-slots / accumulator rows
     const int group = n_q_heads / n_kv_heads;
@@ -159,55 +192,67 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     // tile pair, query head of the group: workgroups that run at the same time on an XCD read
     // the same K/V rows through its L2.
     const int xcd = blockIdx.x % xcds;
-    const long long slot_stride = gridDim.x / xcds;
-    const long long per_item = (long long)(n_kv_heads / xcds) * group;
-    long long item = blockIdx.x / xcds;           // index inside this XCD's list
-    int phase = 0;                                // 0: the late (long) tile of the pair, 1: the early one
-    int it_pair = 0, it_nq = 0;                   // decoded item (uniform)
-    Segment seg;
+    const int slot_stride = gridDim.x / xcds;
+    const int per_item = (n_kv_heads / xcds) * group;    // (the host checked that the item count fits 31 bits)
 
-    // decode `item`/`phase` into sg; returns false when the list is exhausted
-    auto decode = [&](Segment& sg) -> bool {
-        if (item >= items_per_xcd) return false;
-        if (phase == 0) {
-            long long before;
-            int b, n_items;
+    // decode w.item / w.phase into w.seg; false when the list is exhausted
+    auto decode = [&](Walker& w) __attribute__((always_inline)) -> bool {
+        if (w.item >= items_per_xcd) return false;
+        Segment& sg = w.seg;
+        if (w.phase == 0) {
+            int before, b, n_items;
             if (uniform_len > 0) {
                 n_items = items_of(uniform_len);
-                b = (int)(item / (per_item * n_items));
-                before = (long long)b * n_items;
+                b = w.item / (per_item * n_items);
+                before = b * n_items;
             } else {
                 int lo = 0, hi = n_seqs;
                 while (hi - lo > 1) {
                     const int mid = (lo + hi) >> 1;
-                    if (per_item * item_map[mid] <= item) lo = mid; else hi = mid;
+                    if (per_item * item_map[mid] <= w.item) lo = mid; else hi = mid;
                 }
                 b = lo;
                 before = item_map[lo];
                 n_items = item_map[lo + 1] - item_map[lo];
             }
-            const long long rem = item - per_item * before;
-            const int kv_local = (int)(rem / ((long long)n_items * group));
-            const int rem2 = (int)(rem % ((long long)n_items * group));
-            it_pair = rem2 / group;
+            const int rem = w.item - per_item * before;
+            const int kv_local = rem / (n_items * group);
+            const int rem2 = rem % (n_items * group);
+            w.pair = rem2 / group;
             sg.kvh = kv_local * xcds + xcd;
             sg.h = sg.kvh * group + rem2 % group;
             sg.row0 = uniform_len > 0 ? b * uniform_len : seq_offsets[b];
             sg.S = uniform_len > 0 ? uniform_len : seq_offsets[b + 1] - sg.row0;
-            it_nq = (sg.S + kBM - 1) / kBM;
-            sg.q_base = (it_nq - 1 - it_pair) * kBM;
+            w.nq = (sg.S + kBM - 1) / kBM;
+            sg.q_base = (w.nq - 1 - w.pair) * kBM;
         } else {
-            sg.q_base = it_pair * kBM;            // same sequence and head, the early tile
+            sg.q_base = w.pair * kBM;             // same sequence and head, the early tile
         }
+        sg.n_tiles = (min(sg.S, sg.q_base + kBM) + kBN - 1) / kBN;
         return true;
     };
-    // step to the next segment of the list
-    auto advance = [&]() {
-        if (phase == 0 && it_nq - 1 - it_pair != it_pair) {
-            phase = 1;
+    // step to the next segment of the list; false (w unchanged) when there is none
+    auto next_segment = [&](Walker& w) __attribute__((always_inline)) -> bool {
+        Walker n = w;
+        if (n.phase == 0 && n.nq - 1 - n.pair != n.pair) {
+            n.phase = 1;
         } else {
-            phase = 0;
-            item += slot_stride;
+            n.phase = 0;
+            n.item += slot_stride;
+        }
+        if (!decode(n)) return false;
+        n.t = 0;
+        w = n;
+        return true;
+    };
+    // step a load cursor to the next tile of the stream; past the end it stays on the last tile
+    // (the same tile is then simply loaded again into a free slot, which keeps the number of
+    // loads per step constant)
+    auto next_tile = [&](Walker& w) __attribute__((always_inline)) {
+        if (w.t + 1 < w.seg.n_tiles) {
+            ++w.t;
+        } else {
+            next_segment(w);
         }
     };
 
@@ -224,41 +269,28 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         k_goff[i] = (uint32_t)r * tok_bytes + ((l_chunk ^ ((r / kLine) & (T::kChunks - 1))) << 4);
         v_goff[i] = (uint32_t)r * tok_bytes + ((l_chunk ^ (((r / kLine) & (T::kChunks / 4 - 1)) << 2)) << 4);
     }
-    auto load_tile = [&](const Segment& sg, int t, int stage) {
-        char* lds_k = smem + stage * T::kStageBytes + (wave * kInstrPerWave) * 1024;
-        char* lds_v = lds_k + T::kMatBytes;
-        const size_t first = ((size_t)(sg.row0 + t * kBN) * n_kv_heads + sg.kvh) * D * 2;
-        const char* kt = (const char*)k + first;
-        const char* vt = (const char*)v + first;
-        const bool partial = (t + 1) * kBN > sg.S;   // last tile of a ragged sequence: rows past the end re-read row S-1
+    // the K (which == 0) or V tile under the cursor into ring slot `slot`
+    auto load_tile = [&](const Walker& w, int which, int slot) __attribute__((always_inline)) {
+        const Segment& sg = w.seg;
+        char* lds = smem + (which * kRing + slot) * T::kMatBytes + (wave * kInstrPerWave) * 1024;
+        const size_t first = ((size_t)(sg.row0 + w.t * kBN) * n_kv_heads + sg.kvh) * D * 2;
+        const char* src = (const char*)(which == 0 ? k : v) + first;
+        const bool partial = (w.t + 1) * kBN > sg.S;   // last tile of a ragged sequence: rows past the end re-read row S-1
 #pragma unroll
         for (int i = 0; i < kInstrPerWave; ++i) {
-            uint32_t kg = k_goff[i], vg = v_goff[i];
+            uint32_t g = which == 0 ? k_goff[i] : v_goff[i];
             if (partial) {
                 const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
-                const uint32_t back = (uint32_t)max(t * kBN + r - (sg.S - 1), 0) * tok_bytes;
-                kg -= back;
-                vg -= back;
+                g -= (uint32_t)max(w.t * kBN + r - (sg.S - 1), 0) * tok_bytes;
             }
-            lds_dma16(kt, kg, lds_k + i * 1024);
-            lds_dma16(vt, vg, lds_v + i * 1024);
+            lds_dma16(src, g, lds + i * 1024);
         }
-    };
-
-    // query fragments: B operand of S^T = K Q^T, in registers for the whole segment
-    bf16x8 qf[kKSteps];
-    auto load_q = [&](const Segment& sg) {
-        const int row = min(sg.q_base + 32 * wave + li, sg.S - 1);
-        const uint16_t* src = q + ((size_t)(sg.row0 + row) * n_q_heads + sg.h) * D + 8 * gl;
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
     };
 
     // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
     const int krow = (li & ~12) | ((li & 4) << 1) | ((li & 8) >> 1);
     // Byte offset of this lane's K fragment inside a 32-row half: row krow, logical chunk
-    // 2*ks + gl, physical chunk (2*ks + gl) ^ swz.  XOR is bitwise, so the offset for k-step ks
-    // is k_lane ^ (ks << 5): one per-lane constant instead of one register per k-step.
+    // 2*ks + gl, physical chunk (2*ks + gl) ^ swz, i.e. k_lane ^ (ks << 5).
     const int k_lane = krow * T::kRowBytes + ((gl ^ ((krow / kLine) & (T::kChunks - 1))) << 4);
     // V fragments come through the transposing read: this lane supplies the 8-byte word at key
     // 8*gl + ((lane & 15) >> 2) (+4 for the second read) of the 16-key step, head-dim columns
@@ -269,183 +301,265 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     const int v_lane = vrow * T::kRowBytes +
                        (((((vrow / kLine) & (T::kChunks / 4 - 1)) << 2) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) << 4) +
                        8 * (lane & 1);
+    // LDS addresses of the fragments.  The ring slot is part of the register: kaddr points into the
+    // K slot of stream position "kpos", vaddr into the V slot of position "vpos"; both are moved on
+    // by one slot once per stream position (bump_k, bump_v).  The half and the 16-key step are
+    // immediates.
+    int kaddr[NS], vaddr[kDTiles];
+    const int lds0 = (int)(uintptr_t)(lptr_t)smem;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) kaddr[i] = lds0 + (k_lane ^ (i << 5));
+#pragma unroll
+    for (int dt = 0; dt < kDTiles; ++dt)
+        vaddr[dt] = lds0 + (2 * kRing - 1) * T::kMatBytes + (v_lane ^ (dt << 6));     // V ring behind the K ring; last slot
+    int kslot = 0, vslot = kRing - 1;             // wave-uniform
+    auto bump_k = [&]() __attribute__((always_inline)) {
+        const int delta = kslot == kRing - 1 ? -(kRing - 1) * T::kMatBytes : T::kMatBytes;
+        kslot = kslot == kRing - 1 ? 0 : kslot + 1;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) kaddr[i] += delta;
+    };
+    auto bump_v = [&]() __attribute__((always_inline)) {
+        const int delta = vslot == kRing - 1 ? -(kRing - 1) * T::kMatBytes : T::kMatBytes;
+        vslot = vslot == kRing - 1 ? 0 : vslot + 1;
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt) vaddr[dt] += delta;
+    };
 
-    // ---- state of the segment being computed
-    f32x16 oacc[kDTiles];
-    float m_run, l_run;
-    int qlo, qrow;                                // first query position of the wavefront / of this lane
-    auto reset_state = [&](const Segment& sg) {
+    auto k_frag = [&](int half, int i) __attribute__((always_inline)) {
+        return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)(kaddr[i] + 32 * half * T::kRowBytes);
+    };
+    // V fragment i of half `half`: 16-key step 2*half + i / kDTiles, head-dim tile i % kDTiles
+    auto v_frag = [&](int half, int i) __attribute__((always_inline)) {
+        const int p = vaddr[i % kDTiles] + 16 * (2 * half + i / kDTiles) * T::kRowBytes;
+        const s16x4 lo = lds_read_tr(p);
+        const s16x4 hi = lds_read_tr(p + 4 * T::kRowBytes);
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    // ---- registers of the wavefront
+    bf16x8 qf[NS];                                // query fragments: B operand of S^T = K Q^T
+    bf16x8 F[NS];                                 // A-operand fragments (K or V) of the group in flight and, from
+                                                  // slot 0 up, of the group after it: fragment j always sits in F[j]
+    f32x16 oacc[kDTiles];                         // O^T
+    f32x16 s0, s1;                                // logits of the two halves
+    u32x4 p0[2], p1[2];                           // probabilities of the two halves, bf16, two 16-key steps each
+    float m_run, nmc, l_run;                      // exponent reference, -c * reference, row denominators (this lane's keys)
+    float ls0, ls1;                               // partial denominators of the half in flight
+
+    // segment being computed, as seen by this wavefront
+    Segment cs;
+    int qlo = 0, qrow = 0;                        // first query position of the wavefront / of this lane
+    int H = 0;                                    // 32-key halves this wavefront needs (the last one holds the diagonal)
+    int n_my = 0;                                 // key tiles this wavefront takes part in
+    auto enter_segment = [&](const Segment& sg) __attribute__((always_inline)) {
+        cs = sg;
+        qlo = sg.q_base + 32 * rb;
+        qrow = qlo + li;
+        H = qlo / 32 + 1;
+        n_my = qlo < sg.S ? (H + 1) / 2 : 0;
+    };
+    auto load_q = [&](const Segment& sg) __attribute__((always_inline)) {
+        const int row = min(sg.q_base + 32 * rb + li, sg.S - 1);
+        const uint16_t* src = q + ((size_t)(sg.row0 + row) * n_q_heads + sg.h) * D + 8 * gl;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
+    };
+
+    // ---- slices.  Everything below is written in the order it should be issued; a scheduling
+    // barrier after every slice keeps it.
+    // exponentials of logits sv[base + EPS*i ..] into fragment pf (element EPS*i ..)
+    float pend = 0.f;                             // even element waiting for its partner (EPS == 1)
+    auto e_slice = [&](const f32x16& sv, int base, int i, u32x4& pf, float& lsum) __attribute__((always_inline)) {
+        if (EPS == 2) {
+            const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i], c, nmc));
+            const float b = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i + 1], c, nmc));
+            lsum += a;
+            lsum += b;
+            pf[i] = pack_bf16(a, b);
+        } else {
+            const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + i], c, nmc));
+            lsum += a;
+            if (i & 1) pf[i >> 1] = pack_bf16(pend, a); else pend = a;
+        }
+    };
+    auto fence = [&]() __attribute__((always_inline)) { __builtin_amdgcn_sched_barrier(0); };
+
+    // What a group does besides its MFMAs.
+    struct Chunk {                                // a chunk of exponentials: logits se[base ..+7] -> pe, lsum
+        bool on;
+        const f32x16* se;
+        int base;
+        u32x4* pe;
+        float* lsum;
+    };
+    struct Frags {                                // a set of NS fragments in LDS: kind 0 none, 1 K (at kpos), 2 V (at vpos)
+        int kind, half;
+    };
+    auto frag = [&](const Frags& f, int j) __attribute__((always_inline)) -> bf16x8 {
+        return f.kind == 1 ? k_frag(f.half, j) : v_frag(f.half, j);
+    };
+    // fragments 0 .. kLook-1 of a group that no previous group fetched
+    auto prime = [&](const Frags& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kLook; ++j) F[j] = frag(f, j);
+    };
+    // the load of slice i: fragment i + kLook of the own set, or of the next group's set
+    auto slice_load = [&](const Frags& own, const Frags& next, int i) __attribute__((always_inline)) {
+        const int j = i + kLook;
+        if (j < NS) {
+            if (own.kind != 0) F[j] = frag(own, j);
+        } else {
+            if (next.kind != 0) F[j - NS] = frag(next, j - NS);
+        }
+    };
+    // QK group: sd = K_half Q^T
+    auto qk_group = [&](f32x16& sd, const Chunk& e, const Frags& own, const Frags& next) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            if (i == 0) {
+                f32x16 z;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) z[r] = 0.f;
+                sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[0], qf[0], z, 0, 0, 0);
+            } else {
+                sd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[i], qf[i], sd, 0, 0, 0);
+            }
+            if (e.on) e_slice(*e.se, e.base, i, *e.pe, *e.lsum);
+            slice_load(own, next, i);
+            fence();
+        }
+    };
+    // PV group: O^T += V_half^T P_half^T (fragment i: 16-key step i / kDTiles, head-dim tile i % kDTiles)
+    auto pv_group = [&](const u32x4 (&pp)[2], const Chunk& e, const Frags& own, const Frags& next)
+                        __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            oacc[i % kDTiles] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                F[i], __builtin_bit_cast(bf16x8, pp[i / kDTiles]), oacc[i % kDTiles], 0, 0, 0);
+            if (e.on) e_slice(*e.se, e.base, i, *e.pe, *e.lsum);
+            slice_load(own, next, i);
+            fence();
+        }
+    };
+    // a chunk of exponentials alone
+    auto e_group = [&](const f32x16& se, int ebase, u32x4& pe, float& lsum) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) e_slice(se, ebase, i, pe, lsum);
+    };
+    const Chunk no_e = {false, &s0, 0, &p0[0], &ls0};
+    const Frags no_f = {0, 0};
+    const Frags fk0 = {1, 0}, fk1 = {1, 1}, fv0 = {2, 0}, fv1 = {2, 1};
+
+    // causal mask of half number hh (0, 1, 2, ... along the keys) of this wavefront: nothing
+    // below the diagonal half H-1, the triangle inside it, everything beyond it
+    auto mask_half = [&](f32x16& sv, int hh) __attribute__((always_inline)) {
+        if (hh >= H - 1) {
+            const bool all = hh > H - 1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = 16 * (r >> 3) + 8 * gl + (r & 7);
+                if (all || key > li) sv[r] = -INFINITY;
+            }
+        }
+    };
+    // Rare path: some row of the wavefront outgrew the reference by more than 2^16.  Take the
+    // true row maxima of the half, move the reference, rescale what has been accumulated, redo
+    // the half.
+    auto settle_half = [&](const f32x16& sv, u32x4 (&pp)[2], float lsum) __attribute__((always_inline)) {
+        if (__ballot(!(lsum <= 65536.0f)) != 0) {
+            float mx = sv[0];
+#pragma unroll
+            for (int r = 1; r < 16; r += 2) {
+                const float nxt = r + 1 < 16 ? sv[r + 1] : sv[r];
+                mx = fmaxf(fmaxf(mx, sv[r]), nxt);              // v_max3_f32
+            }
+            mx = max_with_other_half(mx);
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+            m_run = m_new;
+            nmc = -m_new * c;
+            lsum = 0.f;
+            e_group(sv, 0, pp[0], lsum);
+            e_group(sv, 8, pp[1], lsum);
+        }
+        l_run += lsum;
+    };
+
+    // First steps of a segment, run while the previous segment's last tile is the current
+    // stream position (kpos = tile 0 of the new segment):
+    //   QK0(0), reference from its true maxima, QK1(0) | E0a(0), E0b(0).
+    auto pre_iteration = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-        m_run = -INFINITY;
         l_run = 0.f;
-        qlo = sg.q_base + 32 * wave;
-        qrow = qlo + li;
-    };
-
-    // One 64-key tile.  The two 32-key halves are two independent instruction streams that
-    // are overlapped inside the wavefront: while the matrix pipe runs QK^T of the second half
-    // the vector pipe exponentiates the first, and while it runs P V of the first half the
-    // vector pipe exponentiates the second.  The tile is written as two pieces, tile_front
-    // (up to the last use of the query fragments) and tile_back, so that the last tile of a
-    // segment can request the next segment's query fragments in between.
-    f32x16 s0, s1;
-    bf16x8 pf[4];
-    bf16x8 vf[kDTiles][2];
-    int kl, vl;
-    const char *Ks, *Vs;
-    int key0, S;
-    auto tile_begin = [&](const Segment& sg, int t, int stage) {
-        Ks = smem + stage * T::kStageBytes;
-        Vs = Ks + T::kMatBytes;
-        key0 = t * kBN;
-        S = sg.S;
-        kl = k_lane;                                     // opaque per tile, see load_tile
-        vl = v_lane;
-        asm volatile("" : "+v"(kl), "+v"(vl));
-    };
-
-        auto k_frag = [&](int half, int ks) { return *(const bf16x8*)(Ks + 32 * half * T::kRowBytes + (kl ^ (ks << 5))); };
-        auto v_frag = [&](int dt, int ks) {
-            const char* p = Vs + 16 * ks * T::kRowBytes + (vl ^ (dt << 6));
-            const s16x4 lo = lds_read_tr(p);
-            const s16x4 hi = lds_read_tr(p + 4 * T::kRowBytes);
-            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        };
-        // causal / end-of-sequence mask of one half (diagonal tiles only; wave-uniform test)
-        auto mask_half = [&](f32x16& sv, int half) {
-            const int kbase = key0 + 32 * half;
-            if ((kbase + 31 > qlo) || (kbase + 32 > S)) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = kbase + 16 * (r >> 3) + 8 * gl + (r & 7);
-                    if (key > qrow || key >= S) sv[r] = -INFINITY;
-                }
-            }
-        };
-        // p = 2^(c s - c m) for one half against the CURRENT reference m: fp32 row sum of this
-        // lane's 16 keys, bf16 fragments for the PV product.  No row maximum is taken: a
-        // reference that has become too small shows up as a huge (or infinite, or NaN) sum.
-        auto half_exp = [&](const f32x16& sv, bf16x8& p0, bf16x8& p1) -> float {
-            const float mc = m_run * c;
-            float lsum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[e], c, -mc));
-                const float b2 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 + e], c, -mc));
-                lsum += a + b2;
-                p0[e] = (__bf16)a;
-                p1[e] = (__bf16)b2;
-            }
-            return lsum;
-        };
-        // Rare path: some row of the wavefront outgrew the reference by more than 2^16 (always
-        // the case on the first tile, where the reference is -inf).  Take the true row maxima,
-        // move the reference, rescale what has been accumulated, redo the half.
-        auto renew_half = [&](const f32x16& sv, bf16x8& p0, bf16x8& p1, float lsum) -> float {
-            if (__ballot(!(lsum <= 65536.0f)) != 0) {
-                float mx = sv[0];
-#pragma unroll
-                for (int r = 1; r < 16; r += 2) {
-                    const float nxt = r + 1 < 16 ? sv[r + 1] : sv[r];
-                    mx = fmaxf(fmaxf(mx, sv[r]), nxt);              // v_max3_f32
-                }
-                mx = max_with_other_half(mx);
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
-                l_run *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-                m_run = m_new;
-                lsum = half_exp(sv, p0, p1);
-            }
-            return lsum;
-        };
-        // Order wanted inside an overlapped region: one MFMA, then a share of the vector work
-        // (a wavefront issues in order, so vector instructions placed behind a dependent MFMA
-        // would wait for it), then a share of the LDS fragment reads of the next region.
-        auto interleave = [&]() {
-#pragma unroll
-            for (int i = 0; i < kKSteps; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x402, 56 / kKSteps, 0);         // VALU + transcendental
-                __builtin_amdgcn_sched_group_barrier(0x100, 2 * kDTiles * 2 / kKSteps, 0);   // DS reads
-            }
-        };
-
-    auto tile_front = [&]() {
-        // ---- R0: S0^T = K0 Q^T (keys 0..31 of the tile)
-        {
-            bf16x8 kf[kKSteps];
-#pragma unroll
-            for (int i = 0; i < kKSteps; ++i) kf[i] = k_frag(0, i);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s0[r] = 0.f;
-#pragma unroll
-            for (int i = 0; i < kKSteps; ++i) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i], s0, 0, 0, 0);
-        }
-        bf16x8 kf1[kKSteps];
-#pragma unroll
-        for (int i = 0; i < kKSteps; ++i) kf1[i] = k_frag(1, i);
-        __builtin_amdgcn_sched_barrier(0);
+        prime(fk0);
+        qk_group(s0, no_e, fk0, fk1);
         mask_half(s0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- R1: S1^T = K1 Q^T on the matrix pipe  ||  exponentials of the first half
+        float mx = s0[0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s1[r] = 0.f;
-#pragma unroll
-        for (int i = 0; i < kKSteps; ++i) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1[i], qf[i], s1, 0, 0, 0);
-        float ls = half_exp(s0, pf[0], pf[1]);
-#pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = v_frag(dt, ks);
-        // keep the exponentials in this region (the optimiser would sink them to their first use)
-        asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(ls));
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        l_run += renew_half(s0, pf[0], pf[1], ls);
+        for (int r = 1; r < 16; r += 2) {
+            const float nxt = r + 1 < 16 ? s0[r + 1] : s0[r];
+            mx = fmaxf(fmaxf(mx, s0[r]), nxt);
+        }
+        m_run = max_with_other_half(mx);          // key 0 is visible to every row: finite
+        nmc = -m_run * c;
+        ls0 = 0.f;
+        fence();
+        const Chunk e0a = {true, &s0, 0, &p0[0], &ls0};
+        qk_group(s1, e0a, fk1, no_f);
+        e_group(s0, 8, p0[1], ls0);
+        l_run += ls0;
         mask_half(s1, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        fence();
     };
-    auto tile_back = [&]() {
-        // ---- R2: O^T += V0^T P0^T on the matrix pipe  ||  exponentials of the second half
-#pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf[ks], oacc[dt], 0, 0, 0);
-        float ls = half_exp(s1, pf[2], pf[3]);
-#pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) vf[dt][ks] = v_frag(dt, 2 + ks);
-        asm volatile("" : "+v"(pf[2]), "+v"(pf[3]), "+v"(ls));
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        l_run += renew_half(s1, pf[2], pf[3], ls);
-        __builtin_amdgcn_sched_barrier(0);
 
-        // ---- R3: O^T += V1^T P1^T
-#pragma unroll
-        for (int dt = 0; dt < kDTiles; ++dt)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf[2 + ks], oacc[dt], 0, 0, 0);
+    // One stream position in the steady state: tile t (probabilities, PV; vpos) and tile t+1
+    // (logits; kpos on entry).  Leaves kpos at tile t+2 with its first fragments in F.
+    auto steady = [&](int t) __attribute__((always_inline)) {
+        const Chunk e1a = {true, &s1, 0, &p1[0], &ls1}, e1b = {true, &s1, 8, &p1[1], &ls1};
+        const Chunk e0a = {true, &s0, 0, &p0[0], &ls0}, e0b = {true, &s0, 8, &p0[1], &ls0};
+        ls1 = 0.f;
+        qk_group(s0, e1a, fk0, fv0);              // QK0(t+1) | E1a(t)
+        pv_group(p0, e1b, fv0, fk1);              // PV0(t)   | E1b(t)
+        settle_half(s1, p1, ls1);
+        mask_half(s0, 2 * t + 2);
+        fence();
+        ls0 = 0.f;
+        qk_group(s1, e0a, fk1, fv1);              // QK1(t+1) | E0a(t+1)
+        bump_k();
+        fence();
+        pv_group(p1, e0b, fv1, fk0);              // PV1(t)   | E0b(t+1)
+        settle_half(s0, p0, ls0);
+        mask_half(s1, 2 * t + 3);
+        fence();
+    };
+    // The wavefront's last tile of the segment: no further logits.
+    auto last = [&]() __attribute__((always_inline)) {
+        const Chunk e1b = {true, &s1, 8, &p1[1], &ls1};
+        ls1 = 0.f;
+        prime(fv0);
+        e_group(s1, 0, p1[0], ls1);
+        fence();
+        pv_group(p0, e1b, fv0, fv1);              // PV0(t) | E1b(t)
+        settle_half(s1, p1, ls1);
+        fence();
+        pv_group(p1, no_e, fv1, no_f);            // PV1(t)
     };
 
     // normalise, round to bf16, store; log2 of the denominator for the score pass
-    auto epilogue = [&](const Segment& sg) {
+    auto epilogue = [&]() __attribute__((always_inline)) {
         const float ltot = sum_with_other_half(l_run);
         const float inv = 1.0f / ltot;
-        if (qrow < sg.S) {
-            uint16_t* dst = out + ((size_t)(sg.row0 + qrow) * n_q_heads + sg.h) * D + 4 * gl;
+        if (qrow < cs.S) {
+            uint16_t* dst = out + ((size_t)(cs.row0 + qrow) * n_q_heads + cs.h) * D + 4 * gl;
 #pragma unroll
             for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
@@ -456,65 +570,86 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
                     *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
                 }
             if (lse != nullptr && gl == 0)
-                lse[(size_t)(sg.row0 + qrow) * n_q_heads + sg.h] = m_run * c + __builtin_amdgcn_logf(ltot);
+                lse[(size_t)(cs.row0 + qrow) * n_q_heads + cs.h] = m_run * c + __builtin_amdgcn_logf(ltot);
         }
     };
 
-    // ---- the walk over this workgroup's segments
-    if (!decode(seg)) return;
-    int g = 0;                                    // tiles issued so far: LDS stage = g & 1
-    load_q(seg);
-    load_tile(seg, 0, 0);
-    while (true) {
-        // The query fragments must have landed before the sweep starts: a register load still
-        // pending at the head of the tile loop would make every iteration wait for ALL
-        // outstanding loads, the tile prefetch included.
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qf[ks]));
-        reset_state(seg);
-        const int n_kv_tiles = (min(seg.S, seg.q_base + kBM) + kBN - 1) / kBN;
-        for (int t = 0; t + 1 < n_kv_tiles; ++t, ++g) {
-            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's share of tile t is in LDS
-            __syncthreads();                      // everyone's share is; everyone left the other stage
-            load_tile(seg, t + 1, (g + 1) & 1);
-            // the wavefront takes part while some key of the tile is visible to its last row
-            if (t * kBN <= qlo + 31) {
-                tile_begin(seg, t, g & 1);
-                tile_front();
-                tile_back();
-            }
-        }
-        // last tile of the segment: the other stage and the query registers go to the next
-        // segment (when the list is exhausted the same fragments are simply fetched again)
-        const int t_last = n_kv_tiles - 1;
-        __builtin_amdgcn_s_waitcnt(0x0f70);
-        __syncthreads();
-        advance();
-        Segment nxt = seg;
-        const bool have_next = decode(nxt);
-        if (have_next) load_tile(nxt, 0, (g + 1) & 1);
-        const bool takes_part = t_last * kBN <= qlo + 31;
-        if (takes_part) {
-            tile_begin(seg, t_last, g & 1);
-            tile_front();
-        }
-        load_q(nxt);
-        if (takes_part) tile_back();
-        ++g;
-        epilogue(seg);
-        if (!have_next) break;
-        seg = nxt;
+    // ---- the walk over this workgroup's stream of key tiles
+    Walker cw;                                    // segment being computed
+    cw.item = blockIdx.x / xcds;
+    cw.phase = 0;
+    cw.pair = cw.nq = cw.t = 0;
+    if (!decode(cw)) return;
+    Walker lc = cw;                               // load cursor: kRing - 1 stream positions ahead
+    Walker nx = cw;                               // the segment after the one being computed
+    bool has_next = next_segment(nx);
+    int lslot = 0;                                // ring slot the next tile pair is loaded into
+
+    // One stream position g, the part every wavefront runs: V(g), K(g+1) and K(g+2) are in LDS
+    // afterwards, K and V of position g + kRing - 1 are requested into the slot of position g-1,
+    // and vpos becomes g.
+    auto top = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0): this wavefront's share of everything requested so far is in LDS
+        __syncthreads();                          // everyone's share is; everyone is done with the slot written next
+        load_tile(lc, 0, lslot);
+        load_tile(lc, 1, lslot);
+        next_tile(lc);
+        lslot = lslot == kRing - 1 ? 0 : lslot + 1;
+        bump_v();
+    };
+
+    enter_segment(cw.seg);
+    load_q(cw.seg);
+#pragma unroll 1
+    for (int p = 0; p < kRing - 1; ++p) {
+        load_tile(lc, 0, lslot);
+        load_tile(lc, 1, lslot);
+        next_tile(lc);
+        ++lslot;
     }
+    __builtin_amdgcn_s_waitcnt(0x0f70);           // vmcnt(0)
+    __syncthreads();
+
+    while (true) {
+        // kpos is tile 0 of the segment cw; the stream position is the one before it
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) asm volatile("" : "+v"(qf[ks]));      // the query fragments have landed
+        if (n_my > 0) pre_iteration();
+        bump_k();
+        if (n_my > 1) prime(fk0);
+        const int n_wg = cw.seg.n_tiles;
+        int t = 0;
+#pragma unroll 1
+        for (; t + 1 < n_my; ++t) {
+            top();
+            steady(t);
+        }
+#pragma unroll 1
+        for (; t < n_wg; ++t) {
+            top();
+            if (t == max(n_my - 1, 0) && has_next) load_q(nx.seg);     // the query fragments are dead from here on
+            if (t + 1 == n_my) {
+                last();
+                epilogue();
+            }
+            if (t + 1 < n_wg) bump_k();           // (the last position's move happens after the next segment's first steps)
+        }
+        if (!has_next) break;
+        cw = nx;
+        has_next = next_segment(nx);
+        enter_segment(cw.seg);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);           // no load may still be writing LDS when the workgroup ends
 }
 
 int device_slots() {
-    static int slots = 0;            // workgroups the device holds at 2 per compute unit
+    static int slots = 0;            // workgroups the device holds at one per compute unit
     if (slots == 0) {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
-        slots = 2 * cus;
+        slots = cus;
     }
     return slots;
 }
@@ -537,8 +672,9 @@ int launch_attention_d(const void* q, const void* k, const void* v, const int32_
         if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
     }
     const int xcds = (s.n_kv_heads % 8 == 0) ? 8 : 1;
-    const long long items_per_xcd = (long long)total_items * s.n_q_heads / xcds;
+    const int32_t items_per_xcd = (int32_t)((long long)total_items * s.n_q_heads / xcds);
     long long per_xcd_slots = device_slots() / xcds;
+    if (per_xcd_slots < 1) per_xcd_slots = 1;
     if (per_xcd_slots > items_per_xcd) per_xcd_slots = items_per_xcd;
     const unsigned grid = (unsigned)(per_xcd_slots * xcds);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), Tile<D>::kLdsBytes, stream,

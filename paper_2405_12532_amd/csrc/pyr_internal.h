@@ -18,7 +18,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Query positions per attention segment; two segments (tiles j and n-1-j of a sequence) form one work item.
-constexpr int kAttnBlockRows = 128;
+constexpr int kAttnBlockRows = 256;
 
 // Every launcher returns PYR_OK or PYR_ERR_LAUNCH; arguments are already validated.
 int launch_gather(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,

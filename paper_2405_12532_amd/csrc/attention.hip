@@ -101,8 +101,12 @@ __device__ __forceinline__ s16x4 lds_read_tr(int lds_addr) {
 // Written in assembly on purpose: the compiler would make every later LDS read wait for ALL
 // outstanding loads of this kind (it cannot tell the ring slots apart).  The kernel orders
 // these loads itself: s_waitcnt vmcnt(0) and a barrier before a slot is read.
-__device__ __forceinline__ void lds_dma16(const char* base, uint32_t voff, char* lds) {
-    const uint32_t m0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+__device__ __forceinline__ void lds_dma16(const char* base_, uint32_t voff, uint32_t lds_addr) {
+    const uint32_t m0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+    const uint64_t b64 = (uint64_t)(uintptr_t)base_;         // wave-uniform by construction: keep it in scalar registers
+    const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b64);          // (the builtin returns a signed int:
+    const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b64 >> 32));  //  widen it unsigned)
+    const char* base = (const char*)(uintptr_t)(((uint64_t)b_hi << 32) | (uint64_t)b_lo);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(m0), "v"(voff), "s"(base) : "memory", "m0");
 }
@@ -261,6 +265,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     // with lane l writing physical chunk l % kChunks of row l / kChunks; the lane therefore
     // fetches the logical chunk that the swizzle stores there.
     const uint32_t tok_bytes = (uint32_t)n_kv_heads * D * 2;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)smem;
     const int l_row = lane / T::kChunks, l_chunk = lane % T::kChunks;
     uint32_t k_goff[kInstrPerWave], v_goff[kInstrPerWave];
 #pragma unroll
@@ -269,22 +274,31 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         k_goff[i] = (uint32_t)r * tok_bytes + ((l_chunk ^ ((r / kLine) & (T::kChunks - 1))) << 4);
         v_goff[i] = (uint32_t)r * tok_bytes + ((l_chunk ^ (((r / kLine) & (T::kChunks / 4 - 1)) << 2)) << 4);
     }
-    // the K (which == 0) or V tile under the cursor into ring slot `slot`
-    auto load_tile = [&](const Walker& w, int which, int slot) __attribute__((always_inline)) {
-        const Segment& sg = w.seg;
-        char* lds = smem + (which * kRing + slot) * T::kMatBytes + (wave * kInstrPerWave) * 1024;
-        const size_t first = ((size_t)(sg.row0 + w.t * kBN) * n_kv_heads + sg.kvh) * D * 2;
-        const char* src = (const char*)(which == 0 ? k : v) + first;
-        const bool partial = (w.t + 1) * kBN > sg.S;   // last tile of a ragged sequence: rows past the end re-read row S-1
+    struct LoadPos { size_t off; int t, S; };     // a tile of the stream, as far as the loads care: byte offset of its
+                                                  // first row and head in k and v, tile number, sequence length
+    auto pos_of = [&](const Walker& w) __attribute__((always_inline)) -> LoadPos {
+        return LoadPos{((size_t)(w.seg.row0 + w.t * kBN) * n_kv_heads + w.seg.kvh) * D * 2, w.t, w.seg.S};
+    };
+    // instruction i of this wavefront's share of the K (which == 0) or V tile at position p, into ring slot `slot`
+    // A tile may reach past the end of a ragged sequence: its rows past the end re-read row S-1.
+    // The per-lane source offsets in force for the K tile and the V tile being requested are
+    // kept in registers (k_eff, v_eff) and only touched when a ragged tile comes or goes.
+    auto ragged = [&](const LoadPos& p) __attribute__((always_inline)) { return (p.t + 1) * kBN > p.S; };
+    uint32_t k_eff[kInstrPerWave], v_eff[kInstrPerWave];
+    bool k_rag = false, v_rag = false;
+    auto set_k_eff = [&](const LoadPos& p) __attribute__((always_inline)) {
+        k_rag = ragged(p);
 #pragma unroll
         for (int i = 0; i < kInstrPerWave; ++i) {
-            uint32_t g = which == 0 ? k_goff[i] : v_goff[i];
-            if (partial) {
-                const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
-                g -= (uint32_t)max(w.t * kBN + r - (sg.S - 1), 0) * tok_bytes;
-            }
-            lds_dma16(src, g, lds + i * 1024);
+            const int r = (wave * kInstrPerWave + i) * kRowsPerInstr + l_row;
+            const uint32_t back = k_rag ? (uint32_t)max(p.t * kBN + r - (p.S - 1), 0) * tok_bytes : 0u;
+            k_eff[i] = k_goff[i] - back;
         }
+    };
+    // instruction i of this wavefront's share of the K (which == 0) or V tile at position p, into ring slot `slot`
+    auto load_piece = [&](const LoadPos& p, int which, int slot, int i) __attribute__((always_inline)) {
+        const uint32_t lds = lds_base + (which * kRing + slot) * T::kMatBytes + (wave * kInstrPerWave + i) * 1024;
+        lds_dma16((const char*)(which == 0 ? k : v) + p.off, which == 0 ? k_eff[i] : v_eff[i], lds);
     };
 
     // K row fed as A-operand row li of a 32-key sub-tile: bits 2 and 3 swapped (see header)
@@ -359,11 +373,87 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         H = qlo / 32 + 1;
         n_my = qlo < sg.S ? (H + 1) / 2 : 0;
     };
+    // The query fragments are requested in assembly: the compiler's wait counter must not see
+    // these loads, or it would wait for every K/V load requested after them as well.  They are
+    // older than the K/V loads of the same stream position, so the wait that lets only the
+    // youngest position's loads stay in flight (wait_q, and every `top`) covers them.
     auto load_q = [&](const Segment& sg) __attribute__((always_inline)) {
         const int row = min(sg.q_base + 32 * rb + li, sg.S - 1);
         const uint16_t* src = q + ((size_t)(sg.row0 + row) * n_q_heads + sg.h) * D + 8 * gl;
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
+        for (int ks = 0; ks < NS; ++ks)
+            asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(qf[ks]) : "v"(src + 16 * ks) : "memory");
+    };
+    auto wait_q = [&]() __attribute__((always_inline)) {
+        if (NS == 8)
+            asm volatile("s_waitcnt vmcnt(%8)"
+                         : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[NS - 4]), "+v"(qf[NS - 3]),
+                           "+v"(qf[NS - 2]), "+v"(qf[NS - 1])
+                         : "n"(2 * kInstrPerWave) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%4)"
+                         : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3])
+                         : "n"(2 * kInstrPerWave) : "memory");
+    };
+
+    // ---- the workgroup's stream of key tiles
+    Walker nx;                                    // walks the list of segments one ahead of the arithmetic
+    nx.item = blockIdx.x / xcds;
+    nx.phase = 0;
+    nx.pair = nx.nq = nx.t = 0;
+    if (!decode(nx)) return;
+    Walker lc = nx;                               // load cursor: the K tile kRing stream positions ahead
+    LoadPos kp = pos_of(lc);                      // its tile,
+    LoadPos vp = kp;                              // and the tile before it: V runs one position behind K
+    set_k_eff(kp);
+#pragma unroll
+    for (int i = 0; i < kInstrPerWave; ++i) v_eff[i] = v_goff[i];
+    enter_segment(nx.seg);                        // cs: the segment being computed; nx: the one after it
+    bool has_next = next_segment(nx);
+    int lslot = 0;                                // ring slot the next K tile is loaded into (V: the slot before it)
+
+    // The loads of one stream position: 2 * kInstrPerWave instructions per wavefront, K first.
+    auto request_piece = [&](int idx) __attribute__((always_inline)) {
+        if (idx < kInstrPerWave) load_piece(kp, 0, lslot, idx);
+        else load_piece(vp, 1, lslot == 0 ? kRing - 1 : lslot - 1, idx - kInstrPerWave);
+    };
+    auto request_end = [&]() __attribute__((always_inline)) {
+        vp = kp;
+        if (lc.t + 1 < lc.seg.n_tiles) {          // next tile of the same segment
+            ++lc.t;
+            ++kp.t;
+            kp.off += (size_t)kBN * tok_bytes;
+        } else {                                  // first tile of the next segment (past the end: the same tile again)
+            next_segment(lc);
+            kp = pos_of(lc);
+        }
+        lslot = lslot == kRing - 1 ? 0 : lslot + 1;
+        if (k_rag || v_rag || ragged(kp)) {       // rare: the V offsets take over what the K tile had, K gets its own
+#pragma unroll
+            for (int i = 0; i < kInstrPerWave; ++i) v_eff[i] = v_goff[i] - (k_goff[i] - k_eff[i]);
+            v_rag = k_rag;
+            set_k_eff(kp);
+        }
+    };
+    auto request = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int idx = 0; idx < 2 * kInstrPerWave; ++idx) request_piece(idx);
+        request_end();
+    };
+    // The synchronisation of stream position g, run by every wavefront once, anywhere between its
+    // last read of K(g+1) and its first read of K(g+2): afterwards K(g+2) and V(g+1) are in LDS and
+    // the slots of K(g) and V(g-1) may be overwritten (by K(g+4) and V(g+3): `request`).  Only the
+    // loads of the youngest position may still be in flight after the wait.
+    // (No wait for this wavefront's LDS reads: the slots written next were last read a whole
+    // stream position ago, and every fragment read then has been consumed by an MFMA since.)
+    // Half of the wavefronts (one of the two on every SIMD) synchronise two groups earlier in
+    // their steady-state step than the other half, which keeps the two wavefronts of a SIMD half
+    // a step apart: while one is between groups (checks, cursor arithmetic, the barrier itself)
+    // the other one feeds the matrix pipe.
+    const bool early_sync = wave >= kNW / 2;
+    auto sync = [&](bool with_q) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * kInstrPerWave) : "memory");
+        if (with_q && has_next) load_q(nx.seg);
     };
 
     // ---- slices.  Everything below is written in the order it should be issued; a scheduling
@@ -372,15 +462,22 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     float pend = 0.f;                             // even element waiting for its partner (EPS == 1)
     auto e_slice = [&](const f32x16& sv, int base, int i, u32x4& pf, float& lsum) __attribute__((always_inline)) {
         if (EPS == 2) {
-            const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i], c, nmc));
-            const float b = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i + 1], c, nmc));
+            float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i], c, nmc));
+            float b = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i + 1], c, nmc));
             lsum += a;
             lsum += b;
             pf[i] = pack_bf16(a, b);
+            asm volatile("" : "+v"(pf[i]), "+v"(lsum));   // computed HERE: the optimiser would sink it to its first use
         } else {
-            const float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + i], c, nmc));
+            float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + i], c, nmc));
             lsum += a;
-            if (i & 1) pf[i >> 1] = pack_bf16(pend, a); else pend = a;
+            asm volatile("" : "+v"(a), "+v"(lsum));       // computed HERE: the optimiser would sink it to its first use
+            if (i & 1) {
+                pf[i >> 1] = pack_bf16(pend, a);
+                asm volatile("" : "+v"(pf[i >> 1]));
+            } else {
+                pend = a;
+            }
         }
     };
     auto fence = [&]() __attribute__((always_inline)) { __builtin_amdgcn_sched_barrier(0); };
@@ -431,7 +528,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         }
     };
     // PV group: O^T += V_half^T P_half^T (fragment i: 16-key step i / kDTiles, head-dim tile i % kDTiles)
-    auto pv_group = [&](const u32x4 (&pp)[2], const Chunk& e, const Frags& own, const Frags& next)
+    // With `loads` every other slice also requests one piece of the stream position being loaded.
+    auto pv_group = [&](const u32x4 (&pp)[2], const Chunk& e, const Frags& own, const Frags& next, bool loads)
                         __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
@@ -439,9 +537,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
                 F[i], __builtin_bit_cast(bf16x8, pp[i / kDTiles]), oacc[i % kDTiles], 0, 0, 0);
             if (e.on) e_slice(*e.se, e.base, i, *e.pe, *e.lsum);
             slice_load(own, next, i);
+            if (loads && (i & 1)) request_piece(i >> 1);
             fence();
         }
     };
+    static_assert(NS / 2 == 2 * kInstrPerWave, "one piece per odd slice covers a stream position");
     // a chunk of exponentials alone
     auto e_group = [&](const f32x16& se, int ebase, u32x4& pe, float& lsum) __attribute__((always_inline)) {
 #pragma unroll
@@ -453,14 +553,14 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
 
     // causal mask of half number hh (0, 1, 2, ... along the keys) of this wavefront: nothing
     // below the diagonal half H-1, the triangle inside it, everything beyond it
+    const int diag = li - 8 * gl;                 // register r of a diagonal half is masked if 16*(r>>3) + (r&7) > diag
     auto mask_half = [&](f32x16& sv, int hh) __attribute__((always_inline)) {
         if (hh >= H - 1) {
-            const bool all = hh > H - 1;
+            int thr = hh > H - 1 ? -1 : diag;
+            asm volatile("" : "+v"(thr));         // (opaque: 16 lane masks hoisted out of the loops would cost 32 scalar registers)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = 16 * (r >> 3) + 8 * gl + (r & 7);
-                if (all || key > li) sv[r] = -INFINITY;
-            }
+            for (int r = 0; r < 16; ++r)
+                if (16 * (r >> 3) + (r & 7) > thr) sv[r] = -INFINITY;
         }
     };
     // Rare path: some row of the wavefront outgrew the reference by more than 2^16.  Take the
@@ -527,16 +627,20 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         const Chunk e1a = {true, &s1, 0, &p1[0], &ls1}, e1b = {true, &s1, 8, &p1[1], &ls1};
         const Chunk e0a = {true, &s0, 0, &p0[0], &ls0}, e0b = {true, &s0, 8, &p0[1], &ls0};
         ls1 = 0.f;
+        bump_v();
         qk_group(s0, e1a, fk0, fv0);              // QK0(t+1) | E1a(t)
-        pv_group(p0, e1b, fv0, fk1);              // PV0(t)   | E1b(t)
+        if (early_sync) sync(false);
+        pv_group(p0, e1b, fv0, fk1, false);       // PV0(t)   | E1b(t)
         settle_half(s1, p1, ls1);
         mask_half(s0, 2 * t + 2);
         fence();
         ls0 = 0.f;
         qk_group(s1, e0a, fk1, fv1);              // QK1(t+1) | E0a(t+1)
+        if (!early_sync) sync(t + 2 == n_my);     // (the query fragments are dead from here on if this was the last QK)
         bump_k();
         fence();
-        pv_group(p1, e0b, fv1, fk0);              // PV1(t)   | E0b(t+1)
+        pv_group(p1, e0b, fv1, fk0, true);        // PV1(t)   | E0b(t+1) | loads of the next stream position
+        request_end();
         settle_half(s0, p0, ls0);
         mask_half(s1, 2 * t + 3);
         fence();
@@ -548,10 +652,10 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         prime(fv0);
         e_group(s1, 0, p1[0], ls1);
         fence();
-        pv_group(p0, e1b, fv0, fv1);              // PV0(t) | E1b(t)
+        pv_group(p0, e1b, fv0, fv1, false);       // PV0(t) | E1b(t)
         settle_half(s1, p1, ls1);
         fence();
-        pv_group(p1, no_e, fv1, no_f);            // PV1(t)
+        pv_group(p1, no_e, fv1, no_f, false);     // PV1(t)
     };
 
     // normalise, round to bf16, store; log2 of the denominator for the score pass
@@ -574,60 +678,32 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         }
     };
 
-    // ---- the walk over this workgroup's stream of key tiles
-    Walker cw;                                    // segment being computed
-    cw.item = blockIdx.x / xcds;
-    cw.phase = 0;
-    cw.pair = cw.nq = cw.t = 0;
-    if (!decode(cw)) return;
-    Walker lc = cw;                               // load cursor: kRing - 1 stream positions ahead
-    Walker nx = cw;                               // the segment after the one being computed
-    bool has_next = next_segment(nx);
-    int lslot = 0;                                // ring slot the next tile pair is loaded into
-
-    // One stream position g, the part every wavefront runs: V(g), K(g+1) and K(g+2) are in LDS
-    // afterwards, K and V of position g + kRing - 1 are requested into the slot of position g-1,
-    // and vpos becomes g.
-    auto top = [&]() __attribute__((always_inline)) {
-        __builtin_amdgcn_s_waitcnt(0x0f70);       // vmcnt(0): this wavefront's share of everything requested so far is in LDS
-        __syncthreads();                          // everyone's share is; everyone is done with the slot written next
-        load_tile(lc, 0, lslot);
-        load_tile(lc, 1, lslot);
-        next_tile(lc);
-        lslot = lslot == kRing - 1 ? 0 : lslot + 1;
-        bump_v();
-    };
-
-    enter_segment(cw.seg);
-    load_q(cw.seg);
-#pragma unroll 1
-    for (int p = 0; p < kRing - 1; ++p) {
-        load_tile(lc, 0, lslot);
-        load_tile(lc, 1, lslot);
-        next_tile(lc);
-        ++lslot;
-    }
-    __builtin_amdgcn_s_waitcnt(0x0f70);           // vmcnt(0)
-    __syncthreads();
+    // ---- the walk
+    load_q(cs);
+    // K(0), K(1), V(0) first, then two more positions; wait for the first three
+#pragma unroll
+    for (int i = 0; i < kInstrPerWave; ++i) load_piece(kp, 0, 0, i);
+    request_end();
+    request();
+    request();
+    request();
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(4 * kInstrPerWave) : "memory");
 
     while (true) {
-        // kpos is tile 0 of the segment cw; the stream position is the one before it
-#pragma unroll
-        for (int ks = 0; ks < NS; ++ks) asm volatile("" : "+v"(qf[ks]));      // the query fragments have landed
+        // kpos is tile 0 of the segment cs; the stream position is the one before it
+        wait_q();
         if (n_my > 0) pre_iteration();
         bump_k();
         if (n_my > 1) prime(fk0);
-        const int n_wg = cw.seg.n_tiles;
+        const int n_wg = cs.n_tiles;
         int t = 0;
 #pragma unroll 1
-        for (; t + 1 < n_my; ++t) {
-            top();
-            steady(t);
-        }
+        for (; t + 1 < n_my; ++t) steady(t);
 #pragma unroll 1
         for (; t < n_wg; ++t) {
-            top();
-            if (t == max(n_my - 1, 0) && has_next) load_q(nx.seg);     // the query fragments are dead from here on
+            bump_v();
+            sync(early_sync ? t == max(n_my - 1, 0) : n_my < 2 && t == 0);     // (with the next segment's queries once the fragments are dead)
+            request();
             if (t + 1 == n_my) {
                 last();
                 epilogue();
@@ -635,9 +711,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
             if (t + 1 < n_wg) bump_k();           // (the last position's move happens after the next segment's first steps)
         }
         if (!has_next) break;
-        cw = nx;
+        enter_segment(nx.seg);
         has_next = next_segment(nx);
-        enter_segment(cw.seg);
     }
     __builtin_amdgcn_s_waitcnt(0x0f70);           // no load may still be writing LDS when the workgroup ends
 }

@@ -5,39 +5,83 @@
 // The weights of the last L' rows are rebuilt from the logits and the row denominators the
 // attention kernel saved (log2 domain), so the S x S matrix is never stored:
 //   A_h[i,t] = 2^(c * q_i.k_t - lse_h[i]).
-// One wavefront owns 64 consecutive key positions of one sequence and walks over every
-// head and every 32-row block of the window; with S^T = K Q^T in the MFMA accumulator a
-// lane holds 16 keys of one window row, adds its probabilities into 2x16 per-lane sums and
-// only at the very end the 32 lanes of each half are added up through LDS in a fixed order.
-// No atomics: the result is bit-reproducible.  All S columns are written, the window's own
-// columns too (so each sequence's scores sum to one).
+// One workgroup owns 64 consecutive key positions of one sequence; its two wavefronts share
+// out the KV heads (so a small batch still fills the chip) and each walks over its heads and,
+// per head, over "steps": one query head x one 32-row block of the window.  With
+// S^T = K Q^T in the MFMA accumulator a lane holds 16 keys of one window row, adds its
+// probabilities into 2x16 per-lane sums, and only at the very end the 32 lanes of each half
+// and the two wavefronts are added up through LDS in a fixed order.  No atomics: the result
+// is bit-reproducible.  All S columns are written, the window's own columns too (so each
+// sequence's scores sum to one).
+//
+// Every byte of K (once, from HBM) and of the window's Q rows (once per 64 keys, from L2)
+// passes the CU's vector L1, and loads into registers get through it at roughly a quarter of
+// the rate of loads that write LDS directly - with them this kernel ran at the pace of that
+// L1, not of HBM.  So all operands take the direct path: a wavefront keeps a private 64 x d K
+// tile, a 32 x d Q tile and 32 row denominators in LDS, fills them with global_load_lds
+// (fully coalesced: 16 lanes per 256-byte row, 16-byte chunks XOR-swizzled against bank
+// conflicts), copies the fragments into registers and at once requests the next tile into
+// the same LDS space, which then arrives while the MFMAs and exponentials of this one run.
 #include "pyr_internal.h"
 
 namespace pyr {
 namespace {
 
-constexpr int kWavesPerBlock = 4;
-constexpr int kKeysPerWave = 64;
+constexpr int kWavesPerBlock = 2;    // head groups
+constexpr int kKeysPerBlock = 64;
+
+typedef __attribute__((address_space(3))) char* lptr_t;
+
+// 64 lanes x 16 bytes (or x 4 bytes) from base + voff[lane] to LDS at lds_addr + 16 (4) * lane.
+// Assembly because the wavefront orders these loads itself with s_waitcnt vmcnt(N); they
+// retire in the order issued.
+__device__ __forceinline__ void lds_dma(const char* base_, uint32_t voff, uint32_t lds_addr, bool dword) {
+    const uint32_t m0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+    const uint64_t b64 = (uint64_t)(uintptr_t)base_;         // wave-uniform by construction: keep it in scalar registers
+    const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b64);          // (the builtin returns a signed int:
+    const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b64 >> 32));  //  widen it unsigned)
+    const char* base = (const char*)(uintptr_t)(((uint64_t)b_hi << 32) | (uint64_t)b_lo);
+    if (dword)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(m0), "v"(voff), "s"(base) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_loads() {      // until at most N of this wavefront's loads are outstanding
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 template <int D>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void score_kernel(
+__global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
     const int32_t* __restrict__ seq_offsets, int32_t n_q_heads, int32_t n_kv_heads, int32_t w, int32_t blocks_per_seq,
     float c, float* __restrict__ scores) {
     constexpr int kKSteps = D / 16;
-    __shared__ float red[kWavesPerBlock][64][17];    // +1 column: conflict-free column sums
+    constexpr int kChunks = D / 8;                  // 16-byte chunks per row
+    constexpr int kRowBytes = D * 2;
+    constexpr int kRowsPerLoad = 64 / kChunks;      // rows one load instruction covers
+    constexpr int kKBytes = 64 * kRowBytes, kQBytes = 32 * kRowBytes, kLseBytes = 256;
+    constexpr int kNK = kKBytes / 1024, kNQ = kQBytes / 1024;       // load instructions per K tile, per Q tile
+    constexpr int kRedBytes = kWavesPerBlock * 2 * 64 * 17 * 4;     // +1 column: conflict-free column sums
+    constexpr int kSmemBytes = kWavesPerBlock * (kKBytes + kQBytes + kLseBytes);
+    static_assert(kSmemBytes >= kRedBytes, "the final reduction reuses the tiles' space");
+    __shared__ __align__(1024) char smem[kSmemBytes];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, gl = lane >> 5;
     const int b = blockIdx.x / blocks_per_seq;
     const int row0 = seq_offsets[b];
     const int S = seq_offsets[b + 1] - row0;
-    const int key_base = ((blockIdx.x % blocks_per_seq) * kWavesPerBlock + wave) * kKeysPerWave;
-    const bool active = key_base < S;                 // wave-uniform
+    const int key_base = (blockIdx.x % blocks_per_seq) * kKeysPerBlock;
+    if (key_base >= S) return;                        // uniform over the workgroup
     const int L = min(w, S);
     const int first_row = S - L;                      // local position of the first window row
     const int n_row_blocks = (L + 31) / 32;
     const int group = n_q_heads / n_kv_heads;
+    const int n_steps = group * n_row_blocks;         // per KV head
+    const int kvh_begin = wave * n_kv_heads / kWavesPerBlock, kvh_end = (wave + 1) * n_kv_heads / kWavesPerBlock;
 
     float acc[2][16];
 #pragma unroll
@@ -45,34 +89,94 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void score_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[sk][r] = 0.f;
 
-    for (int kvh = 0; active && kvh < n_kv_heads; ++kvh) {
+    // ---- this wavefront's LDS: K tile, Q tile (1 KB aligned), then the row denominators
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+    const uint32_t kt = lds0 + wave * (kKBytes + kQBytes), qt = kt + kKBytes;
+    const uint32_t lt = lds0 + kWavesPerBlock * (kKBytes + kQBytes) + wave * kLseBytes;
+
+    // ---- load side: lane -> (row inside an instruction's row group, physical chunk).  The LDS
+    // slot of a lane is fixed by the instruction, so the swizzle picks the global chunk.
+    const int ld_row = lane / kChunks, ld_chunk = lane % kChunks;
+    const uint32_t k_row_bytes = (uint32_t)n_kv_heads * kRowBytes, q_row_bytes = (uint32_t)n_q_heads * kRowBytes;
+    const int last_key = S - 1 - key_base;            // rows past the end of the sequence re-read its last row
+    // (the offsets are recomputed at every use - a few VALU operations per load; kept live they
+    //  would push the kernel past the registers of two wavefronts per SIMD)
+    auto issue_k = [&](int kvh) {
+        const char* base = (const char*)(k + ((size_t)(row0 + key_base) * n_kv_heads + kvh) * D);
+        int lim = last_key;
+        asm volatile("" : "+v"(lim));
+#pragma unroll
+        for (int i = 0; i < kNK; ++i) {
+            const int row = kRowsPerLoad * i + ld_row;
+            lds_dma(base, (uint32_t)min(row, lim) * k_row_bytes + 16 * (ld_chunk ^ (row & (kChunks - 1))), kt + 1024 * i,
+                    false);
+        }
+    };
+    auto issue_q = [&](int kvh, int st) {             // kNQ + 1 instructions
+        const int h = kvh * group + st / n_row_blocks, rb = st % n_row_blocks;
+        const int rb_row0 = first_row + 32 * rb;
+        int last_row = L - 1 - 32 * rb;
+        asm volatile("" : "+v"(last_row));
+        const char* base = (const char*)(q + ((size_t)(row0 + rb_row0) * n_q_heads + h) * D);
+#pragma unroll
+        for (int i = 0; i < kNQ; ++i) {
+            const int row = kRowsPerLoad * i + ld_row;
+            lds_dma(base, (uint32_t)min(row, last_row) * q_row_bytes + 16 * (ld_chunk ^ (row & (kChunks - 1))),
+                    qt + 1024 * i, false);
+        }
+        lds_dma((const char*)(lse + (size_t)(row0 + rb_row0) * n_q_heads + h), (uint32_t)min(li, last_row) * n_q_heads * 4,
+                lt, true);
+    };
+
+    // ---- fragment side: operand row li, logical chunk 2*ks + gl
+    auto frag = [&](uint32_t tile, int row, int ks) {
+        const uint32_t a = tile + row * kRowBytes + (((2 * ks + gl) ^ (row & (kChunks - 1))) << 4);
+        return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a;
+    };
+
+    if (kvh_begin < kvh_end) {
+        issue_k(kvh_begin);
+        issue_q(kvh_begin, 0);
+    }
+    // Outstanding loads at the top of a head: its K tile (oldest), then its first step's rows.
+    for (int kvh = kvh_begin; kvh < kvh_end; ++kvh) {
+        const bool has_next = kvh + 1 < kvh_end;
+        wait_loads<kNQ + 1>();                        // the K tile has landed
         bf16x8 kf[2][kKSteps];
 #pragma unroll
-        for (int sk = 0; sk < 2; ++sk) {
-            const int key = min(key_base + 32 * sk + li, S - 1);
-            const uint16_t* src = k + ((size_t)(row0 + key) * n_kv_heads + kvh) * D + 8 * gl;
+        for (int sk = 0; sk < 2; ++sk)
 #pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) kf[sk][ks] = *(const bf16x8*)(src + 16 * ks);
-        }
-        for (int gi = 0; gi < group; ++gi) {
-            const int h = kvh * group + gi;
-            for (int rb = 0; rb < n_row_blocks; ++rb) {
-                const int qpos = first_row + 32 * rb + li;          // this lane's window row
-                const int qrow = min(qpos, S - 1);
-                if (first_row + 32 * rb + 31 < key_base) continue;  // whole row block precedes the keys
-                const uint16_t* qsrc = q + ((size_t)(row0 + qrow) * n_q_heads + h) * D + 8 * gl;
-                const float lse_row = lse[(size_t)(row0 + qrow) * n_q_heads + h];
-                bf16x8 qf[kKSteps];
+            for (int ks = 0; ks < kKSteps; ++ks) kf[sk][ks] = frag(kt, 32 * sk + li, ks);
+        wait_lds();                                   // fragments are in registers: the tile's space is free
+        if (has_next) issue_k(kvh + 1);
+        for (int st = 0; st < n_steps; ++st) {
+            // the step's rows are older than the next K tile only in the head's first step
+            if (st == 0 && has_next) wait_loads<kNK>(); else wait_loads<0>();
+            bf16x8 qf[kKSteps];
 #pragma unroll
-                for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = *(const bf16x8*)(qsrc + 16 * ks);
+            for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = frag(qt, li, ks);
+            const float lse_row = *(const float __attribute__((address_space(3)))*)(uintptr_t)(lt + 4 * li);
+            wait_lds();
+            if (st + 1 < n_steps) issue_q(kvh, st + 1);
+            else if (has_next) issue_q(kvh + 1, 0);
+
+            const int rb = st % n_row_blocks;
+            const int qpos = first_row + 32 * rb + li;              // this lane's window row
+            if (first_row + 32 * rb + 31 < key_base) continue;      // whole row block precedes the keys
+            // masks are only needed where the keys reach into the window or the row block is ragged
+            const bool plain = key_base + 63 <= first_row + 32 * rb && first_row + 32 * rb + 31 < S;   // uniform
 #pragma unroll
-                for (int sk = 0; sk < 2; ++sk) {
-                    f32x16 s;
+            for (int sk = 0; sk < 2; ++sk) {
+                f32x16 s;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+                for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-                    for (int ks = 0; ks < kKSteps; ++ks)
-                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sk][ks], qf[ks], s, 0, 0, 0);
+                for (int ks = 0; ks < kKSteps; ++ks)
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sk][ks], qf[ks], s, 0, 0, 0);
+                if (plain) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[sk][r] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse_row));
+                } else {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = key_base + 32 * sk + 8 * (r >> 2) + 4 * gl + (r & 3);
@@ -84,23 +188,26 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void score_kernel(
             }
         }
     }
+    // every load issued above has been waited for: nothing is in flight towards LDS here
 
-    // ---- add the 32 window-row lanes of each half, fixed order
+    // ---- add the 32 window-row lanes of each half and the two head groups, fixed order
     const float norm = 1.0f / ((float)n_q_heads * (float)L);
+    float (*red)[2][64][17] = (float (*)[2][64][17])smem;
+    __syncthreads();                                  // both wavefronts are done with their tiles
 #pragma unroll
-    for (int sk = 0; sk < 2; ++sk) {
+    for (int sk = 0; sk < 2; ++sk)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) red[wave][lane][r] = acc[sk][r];
-        __syncthreads();
-        if (active && lane < 32) {
-            // key offset `lane` inside the sub-tile lives in half (lane>>2)&1, register 4*(lane>>3)+(lane&3)
-            const int half = (lane >> 2) & 1, r = 4 * (lane >> 3) + (lane & 3);
-            float sum = 0.f;
-            for (int j = 0; j < 32; ++j) sum += red[wave][32 * half + j][r];
-            const int key = key_base + 32 * sk + lane;
-            if (key < S) scores[row0 + key] = sum * norm;
-        }
-        __syncthreads();
+        for (int r = 0; r < 16; ++r) red[wave][sk][lane][r] = acc[sk][r];
+    __syncthreads();
+    if (lane < 32) {
+        const int sk = wave;                          // wavefront 0 sums the first 32 keys, wavefront 1 the rest
+        // key offset `lane` inside the sub-tile lives in half (lane>>2)&1, register 4*(lane>>3)+(lane&3)
+        const int half = (lane >> 2) & 1, r = 4 * (lane >> 3) + (lane & 3);
+        float sum = 0.f;
+        for (int v = 0; v < kWavesPerBlock; ++v)
+            for (int j = 0; j < 32; ++j) sum += red[v][sk][32 * half + j][r];
+        const int key = key_base + 32 * sk + lane;
+        if (key < S) scores[row0 + key] = sum * norm;
     }
 }
 
@@ -109,9 +216,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void score_kernel(
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
                  const pyr_shape& s, int32_t w, float scale_log2, float* scores, hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
-    const int keys_per_block = kWavesPerBlock * kKeysPerWave;
-    const int32_t blocks_per_seq = (s.max_seqlen + keys_per_block - 1) / keys_per_block;
-    dim3 grid((unsigned)((int64_t)blocks_per_seq * s.n_seqs), 1, 1);
+    const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
+    const int64_t n_blocks = (int64_t)blocks_per_seq * s.n_seqs;
+    if (n_blocks >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)n_blocks, 1, 1);
     if (s.head_dim == 128)
         hipLaunchKernelGGL(score_kernel<128>, grid, dim3(kWavesPerBlock * 64), 0, stream, (const uint16_t*)q,
                            (const uint16_t*)k, lse, seq_offsets_dev, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq,

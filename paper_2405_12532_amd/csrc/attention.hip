@@ -460,6 +460,17 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     // barrier after every slice keeps it.
     // exponentials of logits sv[base + EPS*i ..] into fragment pf (element EPS*i ..)
     float pend = 0.f;                             // even element waiting for its partner (EPS == 1)
+    float last_e = 0.f;                           // the exponential of the slice before (EPS == 1)
+    auto e_use = [&](int j, u32x4& pf, float& lsum) __attribute__((always_inline)) {
+        lsum += last_e;
+        asm volatile("" : "+v"(lsum));
+        if (j & 1) {
+            pf[j >> 1] = pack_bf16(pend, last_e);
+            asm volatile("" : "+v"(pf[j >> 1]));
+        } else {
+            pend = last_e;
+        }
+    };
     auto e_slice = [&](const f32x16& sv, int base, int i, u32x4& pf, float& lsum) __attribute__((always_inline)) {
         if (EPS == 2) {
             float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + 2 * i], c, nmc));
@@ -469,15 +480,13 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
             pf[i] = pack_bf16(a, b);
             asm volatile("" : "+v"(pf[i]), "+v"(lsum));   // computed HERE: the optimiser would sink it to its first use
         } else {
+            // The sum and the bf16 pack of an exponential are issued one slice after it: used
+            // straight away, every exponential costs a wait state.
             float a = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[base + i], c, nmc));
-            lsum += a;
-            asm volatile("" : "+v"(a), "+v"(lsum));       // computed HERE: the optimiser would sink it to its first use
-            if (i & 1) {
-                pf[i >> 1] = pack_bf16(pend, a);
-                asm volatile("" : "+v"(pf[i >> 1]));
-            } else {
-                pend = a;
-            }
+            asm volatile("" : "+v"(a));                   // computed HERE: the optimiser would sink it to its first use
+            if (i > 0) e_use(i - 1, pf, lsum);
+            last_e = a;
+            if (i == NS - 1) e_use(i, pf, lsum);
         }
     };
     auto fence = [&]() __attribute__((always_inline)) { __builtin_amdgcn_sched_barrier(0); };

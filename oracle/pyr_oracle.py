@@ -26,7 +26,8 @@ Section 4.1 (prefill phase), for every sequence of a packed batch:
      decay of p).
 
 Readings taken where the paper leaves a choice (each listed in the design
-notes of this repository): uniform averaging weights; mean over all query
+notes of this repository): averaging weights are an input, uniform unless
+given, normalised by their sum; mean over all query
 heads gives one index set per sequence; with grouped-query attention query
 head h reads key/value head h // (Hq // Hkv); the softmax of a recent row
 runs over all its causal columns, recent ones included; ties in the top-k
@@ -34,8 +35,9 @@ go to the lower position; keep counts are rounded half-up in integers.
 
 Pins (see tests/test_oracle_*.py): brute-force loops on tiny inputs, the
 float64 library attention routine of PyTorch, closed forms for K = 0 and for
-constant V, the row-sum and score-sum invariants, exhaustive top-k on tiny
-score vectors, exact rational arithmetic for the schedule.  No function here
+constant V, the row-sum and score-sum invariants, one-hot and split averaging
+weights, exhaustive top-k on tiny score vectors, exact rational arithmetic for
+the schedule, positions carried through two layers against the composed index.  No function here
 is "parity unpinned" against the mathematics; nothing can be pinned against
 numbers printed in the paper because it prints none for this step.
 """
@@ -50,6 +52,7 @@ __all__ = [
     "consistency_score",
     "select_pvc",
     "gather_rows",
+    "gather_positions",
     "schedule_next",
     "prefill_layer",
 ]
@@ -105,12 +108,16 @@ def causal_attention(q, k, v, scale=None):
     return out
 
 
-def consistency_score(q, k, w, scale=None):
+def consistency_score(q, k, w, scale=None, row_weights=None):
     """Ensemble attention weight of every key of ONE sequence.
 
-    Algorithm 1, A_e = weighted_avg(A[-L:, :-L], dim=-2), with uniform
-    weights and the mean over heads:
-        score[t] = 1/(Hq*L') * sum_h sum_{i=S-L'}^{S-1} A_h[i, t],  L' = min(L, S).
+    Algorithm 1, A_e = weighted_avg(A[-L:, :-L], dim=-2), and the mean over heads:
+        score[t] = 1/Hq * sum_h sum_{i=S-L'}^{S-1} omega_i A_h[i, t] / sum_i omega_i,  L' = min(L, S).
+    row_weights=None gives the uniform average (omega_i = 1).  Otherwise row_weights is a
+    vector of L non-negative numbers, one per row of a full recent window in position order
+    (Section 4.1, prefill phase: more recent rows may be given larger weights; the paper
+    prints no values, so they are an input).  A sequence shorter than the window uses the
+    LAST L' of them: the most recent row always takes row_weights[L-1].
     The vector is returned for ALL S columns (the recent columns too, where
     causality zeroes part of the rows) so that it sums to one; only the
     first S - L' entries are candidates for eviction.
@@ -120,9 +127,18 @@ def consistency_score(q, k, w, scale=None):
     S, Hq, d = q.shape
     L = min(int(w), S)
     rows = np.arange(S - L, S)
+    if row_weights is None:
+        omega = np.ones(L, dtype=np.float64)
+    else:
+        rw = np.asarray(row_weights, dtype=np.float64)
+        if rw.shape != (int(w),) or np.any(rw < 0) or not np.all(np.isfinite(rw)):
+            raise ValueError("row_weights must hold w finite non-negative numbers")
+        omega = rw[int(w) - L:]
+        if not omega.sum() > 0:
+            raise ValueError("the weights of the rows in use must not all be zero")
     # v does not enter the weights; pass k in its place to reuse the routine.
-    _, P = attention_rows(q, k, k, rows, scale)
-    return P.sum(axis=(0, 1)) / float(Hq * L)
+    _, P = attention_rows(q, k, k, rows, scale)         # [Hq, L', S]
+    return np.einsum("hrs,r->s", P, omega) / (float(Hq) * omega.sum())
 
 
 def select_pvc(score, w, keep_len):
@@ -152,6 +168,17 @@ def gather_rows(x, idx):
     return np.asarray(x)[np.asarray(idx, dtype=np.int64)]
 
 
+def gather_positions(pos, idx):
+    """Position ids of the kept tokens: pos[idx].
+
+    Appendix A.2 (Table 5): after tokens are evicted the survivors keep the position
+    encodings they had, gathered with the same index as the keys and values, instead of
+    being renumbered 0..k-1.  Carried through every layer, pos always names the token's
+    place in the original prompt.
+    """
+    return np.asarray(pos)[np.asarray(idx, dtype=np.int64)]
+
+
 def schedule_next(S, w, num, den, floor_len):
     """Keep count for the next layer.
 
@@ -168,17 +195,19 @@ def schedule_next(S, w, num, den, floor_len):
     return min(k, S)
 
 
-def prefill_layer(q, k, v, seq_offsets, w, keep_len, scale=None, hidden=None, out_rows=None):
+def prefill_layer(q, k, v, seq_offsets, w, keep_len, scale=None, hidden=None, out_rows=None, row_weights=None,
+                  pos=None):
     """One layer step over a packed batch.
 
     q: [T, Hq, d]; k, v: [T, Hkv, d]; seq_offsets: int [B+1]; keep_len: int [B];
-    hidden: optional [T, D].  out_rows: None (all rows) or a list with, per
+    hidden: optional [T, D]; row_weights: optional [w] (see consistency_score); pos: optional
+    int [T], position ids of the rows.  out_rows: None (all rows) or a list with, per
     sequence, the local query positions at which `out` is evaluated (the
     scores, the selection and the gathers are always complete).
 
     Returns a dict: out (list per sequence of [n_rows, Hq, d]), out_rows,
     scores [T], kept_idx (global packed rows, int64 [T']), out_offsets [B+1],
-    k_out, v_out, hidden_out.
+    k_out, v_out, hidden_out, pos_out.
     """
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -204,11 +233,11 @@ def prefill_layer(q, k, v, seq_offsets, w, keep_len, scale=None, hidden=None, ou
         o, _ = attention_rows(qb, kb, vb, rows, scale)
         outs.append(o)
         rows_used.append(rows)
-        sb = consistency_score(qb, kb, w, scale)
+        sb = consistency_score(qb, kb, w, scale, row_weights)
         scores[r0:r1] = sb
-        pos = select_pvc(sb, w, keep_len[b])
-        kept.append(pos + r0)
-        out_offsets[b + 1] = out_offsets[b] + pos.shape[0]
+        sel = select_pvc(sb, w, keep_len[b])
+        kept.append(sel + r0)
+        out_offsets[b + 1] = out_offsets[b] + sel.shape[0]
     kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int64)
     res = {
         "out": outs,
@@ -221,4 +250,6 @@ def prefill_layer(q, k, v, seq_offsets, w, keep_len, scale=None, hidden=None, ou
     }
     if hidden is not None:
         res["hidden_out"] = gather_rows(hidden, kept_idx)
+    if pos is not None:
+        res["pos_out"] = gather_positions(pos, kept_idx)
     return res

@@ -143,3 +143,52 @@ def test_score_ignores_rows_before_the_window():
     np.testing.assert_array_equal(orc.consistency_score(q2, k, L), base)
     q3 = q.copy(); q3[S - L] += 3.0
     assert np.abs(orc.consistency_score(q3, k, L) - base).max() > 1e-3
+
+
+# ---- weighted recent rows (Section 4.1, prefill phase: larger weights for more recent rows)
+
+@pytest.mark.parametrize("S,L", [(12, 4), (9, 9), (5, 9), (1, 3)])
+def test_weighted_score_matches_scalar_loops(S, L):
+    Hq, Hkv, d = 4, 2, 4
+    q, k = _rand((S, Hq, d), 30), _rand((S, Hkv, d), 31)
+    rw = np.random.default_rng(32).uniform(0.1, 2.0, L)
+    A = brute_probs(q, k, 1.0 / math.sqrt(d))
+    Le = min(L, S)
+    used = [rw[L - Le + r] for r in range(Le)]          # the most recent row takes the last weight
+    ref = [sum(used[r] * A[h][S - Le + r][t] for h in range(Hq) for r in range(Le)) / (Hq * sum(used)) for t in range(S)]
+    score = orc.consistency_score(q, k, L, row_weights=rw)
+    np.testing.assert_allclose(score, ref, atol=1e-14)
+    assert abs(score.sum() - 1.0) < 1e-13
+
+
+def test_weighted_score_special_cases():
+    S, H, d, L = 24, 3, 8, 6
+    q, k = _rand((S, H, d), 33), _rand((S, H, d), 34)
+    uniform = orc.consistency_score(q, k, L)
+    # equal weights of any size are the plain average
+    np.testing.assert_allclose(orc.consistency_score(q, k, L, row_weights=np.full(L, 3.7)), uniform, atol=1e-15)
+    # all weight on one row: the head-mean of that row of the softmax
+    for r in (0, 2, L - 1):
+        onehot = np.zeros(L); onehot[r] = 5.0
+        _, P = orc.attention_rows(q, k, k, [S - L + r])
+        np.testing.assert_allclose(orc.consistency_score(q, k, L, row_weights=onehot), P[:, 0, :].mean(axis=0), atol=1e-15)
+    # un-normalised sums are additive in the weights
+    a, b = np.array([1.0, 0, 2, 0, 0.5, 0]), np.array([0, 3.0, 0, 1, 0, 4])
+    sa, sb, sab = (orc.consistency_score(q, k, L, row_weights=x) for x in (a, b, a + b))
+    np.testing.assert_allclose(sab * (a + b).sum(), sa * a.sum() + sb * b.sum(), atol=1e-14)
+    # more weight on the last row moves the score towards that row's distribution
+    _, P = orc.attention_rows(q, k, k, [S - 1])
+    last = P[:, 0, :].mean(axis=0)
+    ramp = orc.consistency_score(q, k, L, row_weights=np.arange(1, L + 1))
+    assert np.abs(ramp - last).sum() < np.abs(uniform - last).sum()
+
+
+def test_weighted_score_rejects_bad_weights():
+    q, k = _rand((8, 2, 4), 35), _rand((8, 2, 4), 36)
+    for bad in (np.ones(3), -np.ones(4), np.array([1, np.nan, 1, 1]), np.zeros(4)):
+        with pytest.raises(ValueError):
+            orc.consistency_score(q, k, 4, row_weights=bad)
+    # a short sequence only needs a positive weight among the rows it uses
+    orc.consistency_score(q[:2], k[:2], 4, row_weights=np.array([0, 0, 0, 1.0]))
+    with pytest.raises(ValueError):
+        orc.consistency_score(q[:2], k[:2], 4, row_weights=np.array([1.0, 1, 0, 0]))

@@ -189,3 +189,40 @@ def test_synth_bf16_rounding_is_nearest_even():
     ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     np.testing.assert_array_equal(bits, ref)
     np.testing.assert_array_equal(synth.bf16_bits_to_f32(bits), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+
+
+# ---- position ids of the survivors (Appendix A.2: gathered, not renumbered)
+
+def test_positions_follow_the_tokens_through_two_layers():
+    rng = np.random.default_rng(50)
+    lens = [37, 5, 64]
+    off = np.concatenate([[0], np.cumsum(lens)])
+    T, Hq, Hkv, d, w = int(off[-1]), 2, 1, 8, 4
+    pos0 = np.concatenate([np.arange(n) for n in lens])              # position inside the own prompt
+    q, k, v = (rng.standard_normal((T, h, d)) for h in (Hq, Hkv, Hkv))
+    keep1 = [20, 5, 40]
+    r1 = orc.prefill_layer(q, k, v, off, w, keep1, pos=pos0)
+    # layer 1 starts from 0..S-1, so the carried ids are the local kept indices
+    np.testing.assert_array_equal(r1["pos_out"], r1["kept_idx"] - np.repeat(off[:-1], keep1))
+    for b in range(3):
+        seg = r1["pos_out"][r1["out_offsets"][b]:r1["out_offsets"][b + 1]]
+        assert np.all(np.diff(seg) > 0) and seg[-1] == lens[b] - 1   # ascending, last token always survives
+    # layer 2 on the compacted rows (fresh q/k/v of the new length): ids compose
+    T1 = int(r1["out_offsets"][-1])
+    q2, k2, v2 = (rng.standard_normal((T1, h, d)) for h in (Hq, Hkv, Hkv))
+    keep2 = [9, 4, 17]
+    r2 = orc.prefill_layer(q2, k2, v2, r1["out_offsets"], w, keep2, pos=r1["pos_out"])
+    np.testing.assert_array_equal(r2["pos_out"], pos0[r1["kept_idx"][r2["kept_idx"]]])
+    assert r2["pos_out"].dtype == pos0.dtype
+
+
+def test_layer_with_row_weights_uses_them_per_sequence():
+    rng = np.random.default_rng(51)
+    off = np.array([0, 30, 33])                                      # the second sequence is shorter than the window
+    T, H, d, w = 33, 2, 8, 5
+    q, k, v = (rng.standard_normal((T, H, d)) for _ in range(3))
+    rw = np.array([0.5, 1.0, 1.5, 2.0, 4.0])
+    r = orc.prefill_layer(q, k, v, off, w, [12, 3], row_weights=rw)
+    np.testing.assert_array_equal(r["scores"][:30], orc.consistency_score(q[:30], k[:30], w, row_weights=rw))
+    np.testing.assert_array_equal(r["scores"][30:], orc.consistency_score(q[30:], k[30:], w, row_weights=rw))
+    np.testing.assert_array_equal(r["kept_idx"][:12], orc.select_pvc(r["scores"][:30], w, 12))

@@ -160,6 +160,23 @@ def main():
     torch.cuda.synchronize()
     fused_ms = (time.perf_counter() - t1) * 1e3 / args.steps
 
+    # the optional extras of the step, timed on their own (not part of `value`): recency-weighted
+    # score pass and the gather of the kept tokens' position ids
+    rw = torch.linspace(0.25, 1.0, wl.w, dtype=torch.float32, device="cuda")
+    pos = torch.arange(T, dtype=torch.int32, device="cuda")
+    pos_out = torch.empty(n_kept, dtype=torch.int32, device="cuda")
+    ex = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(-1, args.steps):
+        e = ex[max(i, 0)]
+        e[0].record()
+        pyr.score_weighted(q, k, lse, off_d, off_h, shape, wl.w, 0.0, rw, scores)
+        e[1].record()
+        pyr.gather_positions(pos, kept, n_kept, pos_out)
+        e[2].record()
+    torch.cuda.synchronize()
+    extras_ms = {"score_weighted": float(np.mean([e[0].elapsed_time(e[1]) for e in ex])),
+                 "gather_positions": float(np.mean([e[1].elapsed_time(e[2]) for e in ex]))}
+
     fl = attention_flops(wl.seq_lens, Hq, d)
     att_tflops = fl / (kernel_ms["attention"] * 1e-3) / 1e12
     compact_bytes = 2.0 * n_kept * (2 * kv_row + D * 2) + 4.0 * n_kept * (2 if D > 0 else 1)
@@ -176,7 +193,7 @@ def main():
         "config": {"workload": f"{wl.name}: {wl.n_seqs} seqs x {max(wl.seq_lens)} tokens (T={T}), Hq={Hq}, Hkv={Hkv}, "
                                f"d={d}, hidden={D}, w={wl.w}, kept={n_kept}",
                    "tokens_per_step": T, "kept_rows": n_kept},
-        "kernel_ms": kernel_ms, "ms_per_step_single_entry_point": fused_ms,
+        "kernel_ms": kernel_ms, "extras_ms": extras_ms, "ms_per_step_single_entry_point": fused_ms,
         "roofline": {"kernel": "attention", "bound": "mfma", "achieved": att_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": att_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC.get((wl.name, "attention")),

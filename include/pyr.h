@@ -115,6 +115,23 @@ PYR_API int pyr_score(const void* q, const void* k, const float* lse,
               float* scores, void* stream);
 
 /*
+ * Step 2 with averaging weights (Section 4.1, prefill phase: the ensemble is a weighted
+ * average that may favour the more recent rows; the paper prints no weights, so they are
+ * an argument):
+ *   scores[t] = 1/Hq * sum_h sum_i omega_i A_h[i,t] / sum_i omega_i.
+ *   row_weights_dev    dev fp32 [w], one weight per row of a full recent window in
+ *                      position order (row_weights_dev[w-1]: the last token); a sequence
+ *                      shorter than w uses the last S_b of them.  NULL = uniform, the
+ *                      same as pyr_score.  The values are not checked (they live on the
+ *                      device): they must be finite and >= 0, with a positive sum over
+ *                      the rows in use, else the scores are undefined (NaN or inf).
+ */
+PYR_API int pyr_score_weighted(const void* q, const void* k, const float* lse,
+                       const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                       const pyr_shape* shape, int32_t w, float softmax_scale,
+                       const float* row_weights_dev, float* scores, void* stream);
+
+/*
  * Step 3 - TopP (Algorithm 1, TopP(A_e, p) with a count: Section 3.1.1 calls p
  * a retention ratio): per sequence the keep_len[b]-L' context positions
  * (0 .. S_b-L'-1) with the largest score, ties to the lower position, plus the
@@ -147,6 +164,18 @@ PYR_API int pyr_compact2(const void* src0, void* dst0, const void* src1, void* d
                  const int32_t* kept_idx, int64_t n_kept, void* stream);
 
 /*
+ * Position ids of the kept tokens (Appendix A.2, the "gather" strategy of Table 5: the
+ * survivors keep the position encodings they had instead of being renumbered):
+ *   pos_out[j] = pos[kept_idx[j]]  for j < n_kept.
+ *   pos                dev int32, indexed by packed row; pos_out dev int32 [n_kept], written
+ *   kept_idx           dev int32 [n_kept], every value a valid row of pos
+ * Carried through every layer, pos_out names each row's place in the original prompt.
+ * n_kept == 0 is a no-op.
+ */
+PYR_API int pyr_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept,
+                         int32_t* pos_out, void* stream);
+
+/*
  * The whole layer step (Algorithm 1, body of the loop, prefill phase):
  * pyr_attention -> pyr_score -> pyr_select -> pyr_compact2 on one stream.
  *   scores             dev fp32 [T], written (required: the selection reads it)
@@ -159,6 +188,20 @@ PYR_API int pyr_prefill_layer(const void* q, const void* k, const void* v,
                       const int32_t* keep_len_dev, const int32_t* keep_len_host,
                       void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
                       void* k_out, void* v_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same with the two optional extras: averaging weights for step 2 (see
+ * pyr_score_weighted; NULL = uniform) and position ids gathered alongside K and V
+ * (see pyr_gather_positions; pos and pos_out both NULL skips it).
+ */
+PYR_API int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      const float* row_weights_dev, const int32_t* pos,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, int32_t* pos_out,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus

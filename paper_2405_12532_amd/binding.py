@@ -34,9 +34,13 @@ _SIGNATURES = {
     "pyr_schedule_next": (ctypes.c_int, [_I32, _I32, _I32, _I32, _I32, ctypes.POINTER(_I32)]),
     "pyr_attention": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _F32, _VP, _VP, _VP, _VP]),
     "pyr_score": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP]),
+    "pyr_score_weighted": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP, _VP]),
     "pyr_select": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, _I32, _I32, _VP, _VP, _VP]),
     "pyr_compact": (ctypes.c_int, [_VP, _SZ, _VP, _I64, _VP, _VP]),
     "pyr_compact2": (ctypes.c_int, [_VP, _VP, _VP, _VP, _SZ, _VP, _I64, _VP]),
+    "pyr_gather_positions": (ctypes.c_int, [_VP, _VP, _I64, _VP, _VP]),
+    "pyr_prefill_layer_ex": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
+                                            _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
     "pyr_prefill_layer": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                          _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
 }
@@ -113,6 +117,13 @@ def score(q, k, lse, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale,
            "pyr_score")
 
 
+def score_weighted(q, k, lse, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, row_weights_dev, scores,
+                   stream=None):
+    _check(load().pyr_score_weighted(_ptr(q), _ptr(k), _ptr(lse), _ptr(seq_offsets_dev), _ptr(seq_offsets_host),
+                                     ctypes.byref(shape), int(w), float(softmax_scale), _ptr(row_weights_dev),
+                                     _ptr(scores), _stream(stream)), "pyr_score_weighted")
+
+
 def select(scores, seq_offsets_dev, seq_offsets_host, keep_len_dev, keep_len_host, n_seqs, w, kept_idx,
            out_offsets_dev, stream=None):
     _check(load().pyr_select(_ptr(scores), _ptr(seq_offsets_dev), _ptr(seq_offsets_host), _ptr(keep_len_dev),
@@ -128,6 +139,21 @@ def compact(src, row_bytes, kept_idx, n_kept, dst, stream=None):
 def compact2(src0, dst0, src1, dst1, row_bytes, kept_idx, n_kept, stream=None):
     _check(load().pyr_compact2(_ptr(src0), _ptr(dst0), _ptr(src1), _ptr(dst1), int(row_bytes), _ptr(kept_idx),
                                int(n_kept), _stream(stream)), "pyr_compact2")
+
+
+def gather_positions(pos, kept_idx, n_kept, pos_out, stream=None):
+    _check(load().pyr_gather_positions(_ptr(pos), _ptr(kept_idx), int(n_kept), _ptr(pos_out), _stream(stream)),
+           "pyr_gather_positions")
+
+
+def prefill_layer_ex(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev, keep_len_host,
+                     row_weights_dev, pos, out, scores, kept_idx, out_offsets_dev, k_out, v_out, pos_out, workspace,
+                     workspace_bytes_, stream=None):
+    _check(load().pyr_prefill_layer_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(seq_offsets_dev), _ptr(seq_offsets_host),
+                                       ctypes.byref(shape), int(w), float(softmax_scale), _ptr(keep_len_dev),
+                                       _ptr(keep_len_host), _ptr(row_weights_dev), _ptr(pos), _ptr(out), _ptr(scores),
+                                       _ptr(kept_idx), _ptr(out_offsets_dev), _ptr(k_out), _ptr(v_out), _ptr(pos_out),
+                                       _ptr(workspace), int(workspace_bytes_), _stream(stream)), "pyr_prefill_layer_ex")
 
 
 def prefill_layer(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev, keep_len_host,
@@ -154,10 +180,11 @@ def to_host_bits(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0):
+def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0, row_weights=None, pos=None):
     """Upload the arrays of synth.make_inputs, run pyr_prefill_layer (+ pyr_compact on the
     hidden rows), download everything.  Buffers are allocated with torch; every step of
-    the path runs in the library."""
+    the path runs in the library.  With row_weights (float [w]) and/or pos (int [T]) the
+    call goes through pyr_prefill_layer_ex."""
     import numpy as np
     import torch
     q, k, v = (to_device_bf16(x[n]) for n in ("q", "k", "v"))
@@ -178,9 +205,18 @@ def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0):
     out_off = torch.empty(B + 1, dtype=torch.int32, device="cuda")
     k_out = torch.empty((max(n_kept, 1), Hkv, d), dtype=torch.bfloat16, device="cuda")
     v_out = torch.empty_like(k_out)
-    prefill_layer(q, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, out, scores, kept, out_off,
-                  k_out, v_out, ws, ws_bytes)
     res = {}
+    if row_weights is None and pos is None:
+        prefill_layer(q, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, out, scores, kept, out_off,
+                      k_out, v_out, ws, ws_bytes)
+    else:
+        rw_d = None if row_weights is None else torch.from_numpy(np.ascontiguousarray(row_weights, dtype=np.float32)).cuda()
+        pos_d = None if pos is None else torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).cuda()
+        pos_out = None if pos is None else torch.empty(max(n_kept, 1), dtype=torch.int32, device="cuda")
+        prefill_layer_ex(q, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, rw_d, pos_d, out, scores, kept,
+                         out_off, k_out, v_out, pos_out, ws, ws_bytes)
+        if pos is not None:
+            res["pos_out"] = pos_out.cpu().numpy()[:n_kept]
     if hidden is not None:
         hid = to_device_bf16(hidden)
         hid_out = torch.empty((max(n_kept, 1), hid.shape[1]), dtype=torch.bfloat16, device="cuda")

@@ -88,7 +88,7 @@ const char* pyr_strerror(int status) {
     }
 }
 
-int pyr_version(void) { return 100; }
+int pyr_version(void) { return 200; }
 
 int pyr_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out) {
     if (bytes_out == nullptr) return PYR_ERR_NULL;
@@ -130,10 +130,10 @@ int pyr_attention(const void* q, const void* k, const void* v,
                                  (hipStream_t)stream);
 }
 
-int pyr_score(const void* q, const void* k, const float* lse,
-              const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
-              const pyr_shape* shape, int32_t w, float softmax_scale,
-              float* scores, void* stream) {
+int pyr_score_weighted(const void* q, const void* k, const float* lse,
+                       const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                       const pyr_shape* shape, int32_t w, float softmax_scale,
+                       const float* row_weights_dev, float* scores, void* stream) {
     int rc = check_shape(shape);
     if (rc != PYR_OK) return rc;
     if (w < 1) return PYR_ERR_SHAPE;
@@ -145,7 +145,15 @@ int pyr_score(const void* q, const void* k, const float* lse,
     pyr_shape s = *shape;
     s.max_seqlen = info.max_len;
     return pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, scale_log2(softmax_scale, shape->head_dim),
-                             scores, (hipStream_t)stream);
+                             row_weights_dev, scores, (hipStream_t)stream);
+}
+
+int pyr_score(const void* q, const void* k, const float* lse,
+              const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+              const pyr_shape* shape, int32_t w, float softmax_scale,
+              float* scores, void* stream) {
+    return pyr_score_weighted(q, k, lse, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, nullptr, scores,
+                              stream);
 }
 
 int pyr_select(const float* scores,
@@ -186,6 +194,13 @@ int pyr_compact(const void* src, size_t row_bytes, const int32_t* kept_idx, int6
     return pyr::launch_gather(src, dst, nullptr, nullptr, row_bytes, kept_idx, n_kept, (hipStream_t)stream);
 }
 
+int pyr_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept, int32_t* pos_out, void* stream) {
+    if (n_kept < 0) return PYR_ERR_SHAPE;
+    if (n_kept == 0) return PYR_OK;
+    if (!pos || !kept_idx || !pos_out) return PYR_ERR_NULL;
+    return pyr::launch_gather_positions(pos, kept_idx, n_kept, pos_out, (hipStream_t)stream);
+}
+
 int pyr_prefill_layer(const void* q, const void* k, const void* v,
                       const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
                       const pyr_shape* shape, int32_t w, float softmax_scale,
@@ -193,13 +208,26 @@ int pyr_prefill_layer(const void* q, const void* k, const void* v,
                       void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
                       void* k_out, void* v_out,
                       void* workspace, size_t workspace_bytes, void* stream) {
+    return pyr_prefill_layer_ex(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev,
+                                keep_len_host, nullptr, nullptr, out, scores, kept_idx, out_offsets_dev, k_out, v_out,
+                                nullptr, workspace, workspace_bytes, stream);
+}
+
+int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      const float* row_weights_dev, const int32_t* pos,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, int32_t* pos_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);
     if (rc != PYR_OK) return rc;
     if (w < 1) return PYR_ERR_SHAPE;
     if (!q || !k || !v || !out || !scores || !kept_idx || !out_offsets_dev || !seq_offsets_dev ||
         !seq_offsets_host || !keep_len_dev || !keep_len_host)
         return PYR_ERR_NULL;
-    if ((k_out == nullptr) != (v_out == nullptr)) return PYR_ERR_NULL;
+    if ((k_out == nullptr) != (v_out == nullptr) || (pos == nullptr) != (pos_out == nullptr)) return PYR_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(k_out) || !aligned16(v_out))
         return PYR_ERR_UNSUPPORTED;
     BatchInfo info;
@@ -224,7 +252,7 @@ int pyr_prefill_layer(const void* q, const void* k, const void* v,
 
     rc = pyr::launch_attention(q, k, v, seq_offsets_dev, s, info.uniform_len, info.q_tiles, c, out, lse, tile_map, st);
     if (rc != PYR_OK) return rc;
-    rc = pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, c, scores, st);
+    rc = pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, c, row_weights_dev, scores, st);
     if (rc != PYR_OK) return rc;
     rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
                             out_offsets_dev, st);
@@ -232,7 +260,9 @@ int pyr_prefill_layer(const void* q, const void* k, const void* v,
     if (k_out != nullptr && total_kept > 0) {
         const size_t row_bytes = (size_t)shape->n_kv_heads * shape->head_dim * 2;
         rc = pyr::launch_gather(k, k_out, v, v_out, row_bytes, kept_idx, total_kept, st);
+        if (rc != PYR_OK) return rc;
     }
+    if (pos != nullptr && total_kept > 0) rc = pyr::launch_gather_positions(pos, kept_idx, total_kept, pos_out, st);
     return rc;
 }
 

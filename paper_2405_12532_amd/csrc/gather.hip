@@ -42,7 +42,25 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     }
 }
 
+// Position ids of the kept tokens (Appendix A.2: the survivors keep the position encodings
+// they had; the ids are gathered with the same index as K and V): pos_out[j] = pos[kept_idx[j]].
+__global__ __launch_bounds__(256) void gather_positions_kernel(const int32_t* __restrict__ pos,
+                                                               const int32_t* __restrict__ kept_idx, int64_t n_kept,
+                                                               int32_t* __restrict__ pos_out) {
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < n_kept; j += (int64_t)gridDim.x * blockDim.x)
+        pos_out[j] = pos[kept_idx[j]];
+}
+
 }  // namespace
+
+int launch_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept, int32_t* pos_out,
+                            hipStream_t stream) {
+    if (n_kept == 0) return PYR_OK;
+    int64_t blocks = (n_kept + 255) / 256;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    hipLaunchKernelGGL(gather_positions_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, pos, kept_idx, n_kept, pos_out);
+    return check_launch();
+}
 
 int launch_gather(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
                   const int32_t* kept_idx, int64_t n_kept, hipStream_t stream) {

@@ -32,8 +32,13 @@ int launch_attention(const void* q, const void* k, const void* v, const int32_t*
                      const pyr_shape& shape, int32_t uniform_len, int64_t total_items, float scale_log2,
                      void* out, float* lse, int32_t* item_map, hipStream_t stream);
 
+// row_weights: device [w] or nullptr (uniform)
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
-                 const pyr_shape& shape, int32_t w, float scale_log2, float* scores, hipStream_t stream);
+                 const pyr_shape& shape, int32_t w, float scale_log2, const float* row_weights, float* scores,
+                 hipStream_t stream);
+
+int launch_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept, int32_t* pos_out,
+                            hipStream_t stream);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? PYR_OK : PYR_ERR_LAUNCH; }
 

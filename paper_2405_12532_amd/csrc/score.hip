@@ -1,10 +1,13 @@
 // Ensemble attention weights of the recent window (Algorithm 1,
 // A_e = weighted_avg(A[-L:, :-L], dim=-2); Section 3.2.1), uniform weights, mean over heads:
-//   scores[t] = 1/(Hq*L') * sum_h sum_{i=S-L'}^{S-1} A_h[i, t],   L' = min(w, S).
+//   scores[t] = 1/(Hq*L') * sum_h sum_{i=S-L'}^{S-1} A_h[i, t],   L' = min(w, S),
+// or, with averaging weights omega (Section 4.1: more recent rows may weigh more; one weight
+// per row of a full window, a shorter sequence uses the last L' of them),
+//   scores[t] = 1/Hq * sum_h sum_i omega_i A_h[i, t] / sum_i omega_i.
 //
 // The weights of the last L' rows are rebuilt from the logits and the row denominators the
 // attention kernel saved (log2 domain), so the S x S matrix is never stored:
-//   A_h[i,t] = 2^(c * q_i.k_t - lse_h[i]).
+//   A_h[i,t] = 2^(c * q_i.k_t - lse_h[i]);  a weight enters as  - log2(omega_i)  next to lse_h[i].
 // One workgroup owns 64 consecutive key positions of one sequence; its two wavefronts share
 // out the KV heads (so a small batch still fills the chip) and each walks over its heads and,
 // per head, over "steps": one query head x one 32-row block of the window.  With
@@ -53,19 +56,20 @@ __device__ __forceinline__ void wait_loads() {      // until at most N of this w
 }
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int D>
+template <int D, bool kWeighted>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
     const int32_t* __restrict__ seq_offsets, int32_t n_q_heads, int32_t n_kv_heads, int32_t w, int32_t blocks_per_seq,
-    float c, float* __restrict__ scores) {
+    float c, const float* __restrict__ row_weights, float* __restrict__ scores) {
     constexpr int kKSteps = D / 16;
     constexpr int kChunks = D / 8;                  // 16-byte chunks per row
     constexpr int kRowBytes = D * 2;
     constexpr int kRowsPerLoad = 64 / kChunks;      // rows one load instruction covers
     constexpr int kKBytes = 64 * kRowBytes, kQBytes = 32 * kRowBytes, kLseBytes = 256;
     constexpr int kNK = kKBytes / 1024, kNQ = kQBytes / 1024;       // load instructions per K tile, per Q tile
+    constexpr int kStepLoads = kNQ + (kWeighted ? 2 : 1);           // ... per step: Q tile, denominators, weights
     constexpr int kRedBytes = kWavesPerBlock * 2 * 64 * 17 * 4;     // +1 column: conflict-free column sums
-    constexpr int kSmemBytes = kWavesPerBlock * (kKBytes + kQBytes + kLseBytes);
+    constexpr int kSmemBytes = kWavesPerBlock * (kKBytes + kQBytes + 2 * kLseBytes);
     static_assert(kSmemBytes >= kRedBytes, "the final reduction reuses the tiles' space");
     __shared__ __align__(1024) char smem[kSmemBytes];
 
@@ -89,10 +93,24 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[sk][r] = 0.f;
 
+    // sum of the weights in use (fixed order: every lane strides over them, then a butterfly).
+    // These are the only ordinary loads of the kernel and they are complete before the first
+    // LDS-direct load is issued: the wait counts below assume nothing else is in flight.
+    float weight_sum = (float)L;
+    if (kWeighted) {
+        float part = 0.f;
+        for (int j = lane; j < L; j += 64) part += row_weights[w - L + j];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
+        weight_sum = part;
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(weight_sum) : : "memory");
+    }
+
     // ---- this wavefront's LDS: K tile, Q tile (1 KB aligned), then the row denominators
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
     const uint32_t kt = lds0 + wave * (kKBytes + kQBytes), qt = kt + kKBytes;
-    const uint32_t lt = lds0 + kWavesPerBlock * (kKBytes + kQBytes) + wave * kLseBytes;
+    const uint32_t lt = lds0 + kWavesPerBlock * (kKBytes + kQBytes) + wave * 2 * kLseBytes;   // denominators, then weights
+    const uint32_t wt = lt + kLseBytes;
 
     // ---- load side: lane -> (row inside an instruction's row group, physical chunk).  The LDS
     // slot of a lane is fixed by the instruction, so the swizzle picks the global chunk.
@@ -112,7 +130,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
                     false);
         }
     };
-    auto issue_q = [&](int kvh, int st) {             // kNQ + 1 instructions
+    auto issue_q = [&](int kvh, int st) {             // kStepLoads instructions
         const int h = kvh * group + st / n_row_blocks, rb = st % n_row_blocks;
         const int rb_row0 = first_row + 32 * rb;
         int last_row = L - 1 - 32 * rb;
@@ -126,6 +144,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         }
         lds_dma((const char*)(lse + (size_t)(row0 + rb_row0) * n_q_heads + h), (uint32_t)min(li, last_row) * n_q_heads * 4,
                 lt, true);
+        if (kWeighted) lds_dma((const char*)(row_weights + (w - L) + 32 * rb), (uint32_t)min(li, last_row) * 4, wt, true);
     };
 
     // ---- fragment side: operand row li, logical chunk 2*ks + gl
@@ -141,7 +160,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     // Outstanding loads at the top of a head: its K tile (oldest), then its first step's rows.
     for (int kvh = kvh_begin; kvh < kvh_end; ++kvh) {
         const bool has_next = kvh + 1 < kvh_end;
-        wait_loads<kNQ + 1>();                        // the K tile has landed
+        wait_loads<kStepLoads>();                     // the K tile has landed
         bf16x8 kf[2][kKSteps];
 #pragma unroll
         for (int sk = 0; sk < 2; ++sk)
@@ -155,7 +174,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
             bf16x8 qf[kKSteps];
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = frag(qt, li, ks);
-            const float lse_row = *(const float __attribute__((address_space(3)))*)(uintptr_t)(lt + 4 * li);
+            float lse_row = *(const float __attribute__((address_space(3)))*)(uintptr_t)(lt + 4 * li);
+            if (kWeighted)      // omega * 2^x = 2^(x + log2 omega); a zero weight gives 2^-inf = 0
+                lse_row -= __builtin_amdgcn_logf(*(const float __attribute__((address_space(3)))*)(uintptr_t)(wt + 4 * li));
             wait_lds();
             if (st + 1 < n_steps) issue_q(kvh, st + 1);
             else if (has_next) issue_q(kvh + 1, 0);
@@ -191,7 +212,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     // every load issued above has been waited for: nothing is in flight towards LDS here
 
     // ---- add the 32 window-row lanes of each half and the two head groups, fixed order
-    const float norm = 1.0f / ((float)n_q_heads * (float)L);
+    const float norm = 1.0f / ((float)n_q_heads * weight_sum);
     float (*red)[2][64][17] = (float (*)[2][64][17])smem;
     __syncthreads();                                  // both wavefronts are done with their tiles
 #pragma unroll
@@ -214,20 +235,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 }  // namespace
 
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
-                 const pyr_shape& s, int32_t w, float scale_log2, float* scores, hipStream_t stream) {
+                 const pyr_shape& s, int32_t w, float scale_log2, const float* row_weights, float* scores,
+                 hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
     const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
     const int64_t n_blocks = (int64_t)blocks_per_seq * s.n_seqs;
     if (n_blocks >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
-    dim3 grid((unsigned)n_blocks, 1, 1);
-    if (s.head_dim == 128)
-        hipLaunchKernelGGL(score_kernel<128>, grid, dim3(kWavesPerBlock * 64), 0, stream, (const uint16_t*)q,
-                           (const uint16_t*)k, lse, seq_offsets_dev, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq,
-                           scale_log2, scores);
-    else
-        hipLaunchKernelGGL(score_kernel<64>, grid, dim3(kWavesPerBlock * 64), 0, stream, (const uint16_t*)q,
-                           (const uint16_t*)k, lse, seq_offsets_dev, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq,
-                           scale_log2, scores);
+    dim3 grid((unsigned)n_blocks, 1, 1), block(kWavesPerBlock * 64);
+    auto launch = [&](auto kern) {
+        hipLaunchKernelGGL(kern, grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse, seq_offsets_dev,
+                           s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, scale_log2, row_weights, scores);
+    };
+    if (s.head_dim == 128) {
+        if (row_weights) launch(score_kernel<128, true>); else launch(score_kernel<128, false>);
+    } else {
+        if (row_weights) launch(score_kernel<64, true>); else launch(score_kernel<64, false>);
+    }
     return check_launch();
 }
 

@@ -120,3 +120,17 @@ def test_select_tiny_and_denormal_scores(lib):
     scores = rng.random(4096, dtype=np.float32) * np.float32(1e-38)
     scores[100:200] = 0.0
     _select_case(lib, [4096], 64, [2000], scores.astype(np.float32))
+
+
+@pytest.mark.parametrize("n_src,n_kept", [(1, 1), (1000, 777), (3_000_000, 2_500_001)])
+def test_gather_positions_bit_exact(lib, n_src, n_kept):
+    rng = np.random.default_rng(n_kept)
+    pos = rng.integers(-(1 << 31), 1 << 31, n_src, dtype=np.int64).astype(np.int32)
+    idx = np.sort(rng.choice(n_src, n_kept, replace=False)).astype(np.int32)
+    pos_d, idx_d = torch.from_numpy(pos).cuda(), torch.from_numpy(idx).cuda()
+    out = torch.full((n_kept + 8,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    lib.gather_positions(pos_d, idx_d, n_kept, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:n_kept], pos[idx])
+    assert np.all(got[n_kept:] == 0x5A5A5A5A), "nothing is written past n_kept"

@@ -11,12 +11,14 @@ torch = pytest.importorskip("torch")
 F64 = synth.bf16_bits_to_f64
 
 
-def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=None):
+def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=None, row_weights=None, pos=None):
     x = synth.make_inputs(wl, layer=layer) if x is None else x
     hid = x.get("hidden") if hidden else None
-    res = lib.prefill_layer_from_numpy(x, wl.w, hidden=hid, softmax_scale=scale)
+    res = lib.prefill_layer_from_numpy(x, wl.w, hidden=hid, softmax_scale=scale, row_weights=row_weights, pos=pos)
     ref = orc.prefill_layer(F64(x["q"]), F64(x["k"]), F64(x["v"]), x["seq_offsets"], wl.w, x["keep_len"],
-                            scale=scale if scale > 0 else None, out_rows=out_rows)
+                            scale=scale if scale > 0 else None, out_rows=out_rows, row_weights=row_weights, pos=pos)
+    if pos is not None:
+        assert np.array_equal(res["pos_out"], pos[res["kept_idx"]]), "position ids must follow the kept rows exactly"
     mx, mean = parity.check_out(res["out"], ref, x["seq_offsets"], F64)
     rel = parity.check_scores(res["scores"], ref)
     same, swapped = parity.check_index_sets(res["kept_idx"], ref, x["seq_offsets"], x["keep_len"], wl.w)
@@ -132,3 +134,49 @@ def test_cfg5_gqa_reduced(lib):
     """Config 5's recipe (64 query / 8 KV heads, w 128, keep 0.5) at S 4096, batch 2."""
     wl = synth.shrunk(synth.workload("cfg5"), (4096, 4096))
     run_and_check(lib, wl, out_rows=sample_rows(wl, 8, 3))
+
+
+# --------------------------------------------------------------------------- averaging weights, position ids
+def _weights(kind, w, seed=0):
+    if kind == "ramp":                       # more recent rows weigh more
+        return np.arange(1, w + 1, dtype=np.float32) / w
+    if kind == "last":                       # only the last token's row
+        return np.eye(1, w, w - 1, dtype=np.float32)[0] * 2.5
+    if kind == "gaps":                       # zeros inside, wide dynamic range
+        rw = np.random.default_rng(seed).uniform(0.0, 1.0, w).astype(np.float32) ** 4
+        rw[::3] = 0.0
+        rw[-1] = 1.0
+        return rw
+    return np.full(w, 0.37, dtype=np.float32)   # equal weights: the plain average
+
+
+@pytest.mark.parametrize("kind", ["ramp", "last", "gaps", "equal"])
+@pytest.mark.parametrize("lens,Hq,Hkv,d,w", [
+    ((300, 97, 513, 20), 4, 2, 128, 32),      # ragged, GQA 2, one sequence shorter than the window
+    ((1, 2, 31, 33, 64, 65), 2, 2, 64, 16),   # tiny sequences, d 64
+    ((1000, 40), 16, 8, 128, 100),            # window not a multiple of 32, a sequence of S < w
+])
+def test_weighted_recent_rows(lib, kind, lens, Hq, Hkv, d, w):
+    wl = synth.shrunk(synth.workload("cfg2"), lens, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, w=w, hidden_dim=128)
+    rw = _weights(kind, w)
+    res, ref, x = run_and_check(lib, wl, row_weights=rw)
+    if kind == "equal":                       # and it is the same as the entry point without weights
+        plain = lib.prefill_layer_from_numpy(x, wl.w)
+        np.testing.assert_allclose(res["scores"], plain["scores"], rtol=2e-6, atol=1e-12)
+
+
+def test_weighted_scores_at_bench_shape_sampled(lib):
+    """Full heads and head dim of the 64x2k workload, four sequences: weights through pyr_score_weighted."""
+    wl = synth.shrunk(synth.workload("64x2k"), (2048, 2048, 1500, 2048))
+    rw = np.linspace(0.25, 1.0, wl.w).astype(np.float32)
+    run_and_check(lib, wl, out_rows=sample_rows(wl, 4, 7), row_weights=rw, hidden=False)
+
+
+def test_positions_follow_kept_rows(lib):
+    wl = synth.shrunk(synth.workload("cfg2"), (300, 97, 513, 20), n_q_heads=4, n_kv_heads=2, head_dim=128, w=32,
+                      hidden_dim=128)
+    T = sum(wl.seq_lens)
+    pos = np.random.default_rng(5).integers(0, 1 << 30, T).astype(np.int32)     # arbitrary ids, not 0..S-1
+    res, ref, _ = run_and_check(lib, wl, pos=pos)
+    if np.array_equal(res["kept_idx"], ref["kept_idx"]):
+        assert np.array_equal(res["pos_out"], ref["pos_out"])

@@ -178,6 +178,8 @@ class PyramidChain:
         self.hid0 = synth.make_hidden(synth.shrunk(self.base, (S,) * B))
         self.hid_dev = lib.to_device_bf16(self.hid0)
         self.origin = np.arange(B * S, dtype=np.int64)      # original packed row of every surviving row
+        # position ids carried on the device (Appendix A.2): position inside the own prompt
+        self.pos_dev = torch.arange(S, dtype=torch.int32, device="cuda").repeat(B)
         self.lengths = [S]
         self.next_layer = 0
         self.worst = [0.0, 0.0, 0.0]
@@ -204,6 +206,9 @@ class PyramidChain:
             msg = f", oracle on {seqs}: out max {mx:.2e}, score rel {rel:.2e}, {same}/{len(seqs)} identical sets"
         self.origin = self.origin[kept]
         self.hid_dev = dl.hidden_out
+        pos_out = torch.empty(dl.n_kept, dtype=torch.int32, device="cuda")
+        lib.gather_positions(self.pos_dev, dl.kept, dl.n_kept, pos_out)
+        self.pos_dev = pos_out
         self.lengths.append(int(x["keep_len"][0]))
         self.next_layer += 1
         print(f"  layer {layer:2d}: S {S} -> {self.lengths[-1]}{msg}, {time.time() - t0:.0f} s", flush=True)
@@ -231,5 +236,7 @@ def test_cfg3_pyramid_chain(chain, last_layer):
         assert chain.lengths == [int(t) for t in golden]
         # the surviving hidden rows are the original rows at the composed positions
         assert np.array_equal(chain.lib.to_host_bits(chain.hid_dev), chain.hid0[chain.origin])
+        # ... and the position ids carried through 32 gathers name those original places
+        assert np.array_equal(chain.pos_dev.cpu().numpy(), chain.origin % chain.base.seq_lens[0])
         print(f"[cfg3 chain] worst out max {chain.worst[0]:.2e} mean {chain.worst[1]:.2e}, "
               f"score rel {chain.worst[2]:.2e}, swapped in band {chain.swapped}", flush=True)

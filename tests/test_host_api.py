@@ -124,3 +124,26 @@ def test_compact_and_select_reject_bad_arguments():
     assert lib.pyr_select(0x1000, 0x2000, off.data_ptr(), 0x3000, keep.data_ptr(), 2, 2, 0x4000, 0x5000, None) == -4
     assert lib.pyr_select(0x1000, 0x2000, off.data_ptr(), 0x3000, keep.data_ptr(), 2, 0, 0x4000, 0x5000, None) == -2
     assert lib.pyr_select(None, 0x2000, off.data_ptr(), 0x3000, keep.data_ptr(), 2, 2, 0x4000, 0x5000, None) == -1
+
+
+def test_position_and_weight_entry_points_reject_bad_arguments():
+    lib = binding.load()
+    assert lib.pyr_gather_positions(0x1000, 0x2000, -1, 0x3000, None) == -2
+    assert lib.pyr_gather_positions(0x1000, 0x2000, 0, 0x3000, None) == 0          # nothing to do, nothing launched
+    assert lib.pyr_gather_positions(None, 0x2000, 3, 0x3000, None) == -1
+    assert lib.pyr_gather_positions(0x1000, 0x2000, 3, None, None) == -1
+    shape = binding.make_shape(2, 30, 20, 4, 2, 64)
+    off, keep = Host([0, 10, 30]), Host([6, 12])
+
+    def layer_ex(pos, pos_out, offsets=off):
+        return lib.pyr_prefill_layer_ex(
+            0x10000, 0x20000, 0x30000, 0x50000, offsets.data_ptr(), ctypes.byref(shape), 4, 0.0, 0x60000,
+            keep.data_ptr(), 0xD0000, pos, 0x70000, 0x80000, 0x90000, 0xA0000, 0xB0000, 0xC0000, pos_out,
+            0x40000, 1 << 20, None)
+    assert layer_ex(0xE0000, None) == -1                                            # ids in but nowhere to put them
+    assert layer_ex(None, 0xF0000) == -1
+    assert layer_ex(0xE0000, 0xF0000, Host([0, 12, 11])) == -5                      # same checks as pyr_prefill_layer
+    assert lib.pyr_score_weighted(0x1000, 0x2000, None, 0x3000, off.data_ptr(), ctypes.byref(shape), 4, 0.0, 0x4000,
+                                  0x5000, None) == -1
+    assert lib.pyr_score_weighted(0x1000, 0x2000, 0x6000, 0x3000, off.data_ptr(), ctypes.byref(shape), 0, 0.0, 0x4000,
+                                  0x5000, None) == -2

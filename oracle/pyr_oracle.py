@@ -37,7 +37,9 @@ Pins (see tests/test_oracle_*.py): brute-force loops on tiny inputs, the
 float64 library attention routine of PyTorch, closed forms for K = 0 and for
 constant V, the row-sum and score-sum invariants, one-hot and split averaging
 weights, exhaustive top-k on tiny score vectors, exact rational arithmetic for
-the schedule, positions carried through two layers against the composed index.  No function here
+the schedule, positions carried through two layers against the composed index,
+the generation-phase update against the prefill step on the same rows and against
+scalar loops.  No function here
 is "parity unpinned" against the mathematics; nothing can be pinned against
 numbers printed in the paper because it prints none for this step.
 """
@@ -55,6 +57,7 @@ __all__ = [
     "gather_positions",
     "schedule_next",
     "prefill_layer",
+    "decode_update",
 ]
 
 
@@ -250,6 +253,55 @@ def prefill_layer(q, k, v, seq_offsets, w, keep_len, scale=None, hidden=None, ou
     }
     if hidden is not None:
         res["hidden_out"] = gather_rows(hidden, kept_idx)
+    if pos is not None:
+        res["pos_out"] = gather_positions(pos, kept_idx)
+    return res
+
+
+def decode_update(q_win, k, v, seq_offsets, w, keep_len, scale=None, row_weights=None, pos=None):
+    """Generation-phase update of one layer's compressed cache (Algorithm 1 run with a
+    non-empty cache: KV = cat(PvC_past, KV); Section 4.1, generation phase: the recent
+    window slides over the newly generated tokens and the PvC is selected again, "the
+    operation is the same as the prefill phase").
+
+    k, v: [T, Hkv, d], the packed caches AFTER the new tokens' rows were appended: per
+    sequence the kept context rows followed by the recent rows, S_b rows in all.
+    q_win: [B, w, Hq, d], the queries of the recent rows, right-aligned: q_win[b, w-1] is
+    the newest token's query; a sequence with S_b < w uses the last S_b slots.
+    Row i of the window (cache row S_b - L' + i) sees every cache row up to itself.
+    The ensemble weights, the selection and the gathers are those of the prefill step.
+    Returns scores [T], kept_idx, out_offsets, k_out, v_out (and pos_out).
+    """
+    q_win = np.asarray(q_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    seq_offsets = np.asarray(seq_offsets, dtype=np.int64)
+    keep_len = np.asarray(keep_len, dtype=np.int64)
+    B = seq_offsets.shape[0] - 1
+    T = k.shape[0]
+    w = int(w)
+    assert q_win.shape[0] == B and q_win.shape[1] == w
+    scores = np.zeros(T, dtype=np.float64)
+    kept = []
+    out_offsets = np.zeros(B + 1, dtype=np.int64)
+    for b in range(B):
+        r0, r1 = int(seq_offsets[b]), int(seq_offsets[b + 1])
+        S = r1 - r0
+        if S == 0:
+            out_offsets[b + 1] = out_offsets[b]
+            continue
+        L = min(w, S)
+        # the score only reads the last L' query rows: place them there, the rest is never touched
+        qb = np.full((S,) + q_win.shape[2:], np.nan)
+        qb[S - L:] = q_win[b, w - L:]
+        sb = consistency_score(qb, k[r0:r1], w, scale, row_weights)
+        scores[r0:r1] = sb
+        sel = select_pvc(sb, w, keep_len[b])
+        kept.append(sel + r0)
+        out_offsets[b + 1] = out_offsets[b] + sel.shape[0]
+    kept_idx = np.concatenate(kept) if kept else np.zeros(0, dtype=np.int64)
+    res = {"scores": scores, "kept_idx": kept_idx, "out_offsets": out_offsets,
+           "k_out": gather_rows(k, kept_idx), "v_out": gather_rows(v, kept_idx)}
     if pos is not None:
         res["pos_out"] = gather_positions(pos, kept_idx)
     return res

@@ -1,6 +1,7 @@
 """Pins of the oracle's selection, gather, schedule and whole layer step (CPU only)."""
 from fractions import Fraction
 import itertools
+import math
 import os
 
 import numpy as np
@@ -226,3 +227,71 @@ def test_layer_with_row_weights_uses_them_per_sequence():
     np.testing.assert_array_equal(r["scores"][:30], orc.consistency_score(q[:30], k[:30], w, row_weights=rw))
     np.testing.assert_array_equal(r["scores"][30:], orc.consistency_score(q[30:], k[30:], w, row_weights=rw))
     np.testing.assert_array_equal(r["kept_idx"][:12], orc.select_pvc(r["scores"][:30], w, 12))
+
+
+# ---- generation-phase update of the compressed cache (Section 4.1, generation phase)
+
+def test_decode_update_equals_the_prefill_step_on_the_same_rows():
+    """With the whole prompt still in the cache and the window's queries handed over, the update is the
+    prefill step's score, selection and gather."""
+    rng = np.random.default_rng(60)
+    lens = [40, 3, 17]
+    off = np.concatenate([[0], np.cumsum(lens)])
+    T, Hq, Hkv, d, w = int(off[-1]), 4, 2, 8, 6
+    q, k, v = (rng.standard_normal((T, h, d)) for h in (Hq, Hkv, Hkv))
+    keep = [20, 3, 9]
+    rw = np.array([0.2, 0.4, 0.6, 0.8, 1.0, 3.0])
+    pos = np.arange(T) * 7
+    q_win = np.full((3, w, Hq, d), np.nan)                   # unused slots must never be read
+    for b, S in enumerate(lens):
+        L = min(w, S)
+        q_win[b, w - L:] = q[off[b + 1] - L:off[b + 1]]
+    pre = orc.prefill_layer(q, k, v, off, w, keep, row_weights=rw, pos=pos)
+    dec = orc.decode_update(q_win, k, v, off, w, keep, row_weights=rw, pos=pos)
+    for name in ("scores", "kept_idx", "out_offsets", "k_out", "v_out", "pos_out"):
+        np.testing.assert_array_equal(dec[name], pre[name])
+
+
+def test_decode_update_matches_scalar_loops():
+    """A cache that is NOT a prompt prefix (context rows are an arbitrary subset): every window row sees all
+    context rows and the window rows up to itself."""
+    rng = np.random.default_rng(61)
+    n_ctx, w, H, d = 9, 4, 2, 4
+    S = n_ctx + w
+    k, v = rng.standard_normal((S, 1, d)), rng.standard_normal((S, 1, d))
+    q_win = rng.standard_normal((1, w, H, d))
+    sc = 1.0 / math.sqrt(d)
+    ref = [0.0] * S
+    for h in range(H):
+        for r in range(w):
+            i = n_ctx + r
+            logits = [sc * sum(q_win[0, r, h, c] * k[j, 0, c] for c in range(d)) for j in range(i + 1)]
+            mx = max(logits)
+            ex = [math.exp(x - mx) for x in logits]
+            for j in range(i + 1):
+                ref[j] += ex[j] / sum(ex) / (H * w)
+    dec = orc.decode_update(q_win, k, v, [0, S], w, [7])
+    np.testing.assert_allclose(dec["scores"], ref, atol=1e-14)
+    top3 = sorted(sorted(range(n_ctx), key=lambda j: (-ref[j], j))[:3])
+    assert dec["kept_idx"].tolist() == top3 + list(range(n_ctx, S))
+    np.testing.assert_array_equal(dec["k_out"], k[dec["kept_idx"]])
+
+
+def test_decode_update_fixed_budget_over_many_steps():
+    """Unbounded input with a fixed number of PvCs (Section 4.1): append one token, update, repeat; the cache
+    never grows past the budget, the window is always the newest w tokens, ids stay ascending."""
+    rng = np.random.default_rng(62)
+    w, H, d, budget = 4, 2, 4, 10
+    k = rng.standard_normal((6, 1, d)); v = rng.standard_normal((6, 1, d))
+    pos = np.arange(6)
+    qs = [rng.standard_normal((H, d)) for _ in range(6)]     # queries of the tokens seen so far
+    for step in range(6, 40):
+        k = np.concatenate([k, rng.standard_normal((1, 1, d))]); v = np.concatenate([v, rng.standard_normal((1, 1, d))])
+        pos = np.concatenate([pos, [step]]); qs.append(rng.standard_normal((H, d)))
+        S = k.shape[0]
+        q_win = np.stack(qs[-w:])[None]
+        keep = orc.schedule_next(S, w, 1, 1, 0) if S <= budget else budget
+        r = orc.decode_update(q_win, k, v, [0, S], w, [keep], pos=pos)
+        k, v, pos = r["k_out"], r["v_out"], r["pos_out"]
+        assert k.shape[0] == min(S, budget)
+        assert pos[-w:].tolist() == list(range(step - w + 1, step + 1)) and np.all(np.diff(pos) > 0)

@@ -176,6 +176,22 @@ def main():
     torch.cuda.synchronize()
     extras_ms = {"score_weighted": float(np.mean([e[0].elapsed_time(e[1]) for e in ex])),
                  "gather_positions": float(np.mean([e[1].elapsed_time(e[2]) for e in ex]))}
+    # generation-phase update of a cache of the same size: the window's queries in their own buffer,
+    # row statistics + fold + score + select + gathers in one call
+    q_win = torch.stack([q[int(off_h[b + 1]) - wl.w:int(off_h[b + 1])] for b in range(wl.n_seqs)]).contiguous() \
+        if min(wl.seq_lens) >= wl.w else None
+    if q_win is not None:
+        dws_bytes = pyr.decode_workspace_bytes(shape, wl.w)
+        dws = torch.empty(dws_bytes, dtype=torch.uint8, device="cuda")
+        de = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        for i in range(-1, args.steps):
+            e = de[max(i, 0)]
+            e[0].record()
+            pyr.decode_update(q_win, k, v, off_d, off_h, shape, wl.w, 0.0, keep_d, keep_h, None, pos, scores, kept,
+                              out_off, k_out, v_out, pos_out, dws, dws_bytes)
+            e[1].record()
+        torch.cuda.synchronize()
+        extras_ms["decode_update"] = float(np.mean([e[0].elapsed_time(e[1]) for e in de]))
 
     fl = attention_flops(wl.seq_lens, Hq, d)
     att_tflops = fl / (kernel_ms["attention"] * 1e-3) / 1e12

@@ -204,6 +204,38 @@ PYR_API int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
                       void* k_out, void* v_out, int32_t* pos_out,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Generation-phase update of one layer's compressed cache (Algorithm 1 with a non-empty
+ * cache, KV = cat(PvC_past, KV); Section 4.1, generation phase: the recent window slides
+ * over the generated tokens and the PvC is selected again with the prefill phase's
+ * operation; with a constant keep_len the cache stays at a fixed size for any input length).
+ *   k, v               dev bf16 [T,Hkv,d]: the packed caches with the new tokens' rows
+ *                      already appended - per sequence its kept context rows, then its
+ *                      recent rows, S_b rows in all (seq_offsets as elsewhere)
+ *   q_win              dev bf16 [B,w,Hq,d]: the queries of the recent rows, right-aligned:
+ *                      q_win[b,w-1] belongs to the newest token (cache row S_b-1); a
+ *                      sequence with S_b < w uses the last S_b slots, the others are not read
+ *   row_weights_dev    as in pyr_score_weighted, NULL = uniform;  pos / pos_out as in
+ *                      pyr_prefill_layer_ex, both NULL skips them
+ *   scores             dev fp32 [T], written: window row i (cache row S_b-L'+i) sees the
+ *                      cache rows 0 .. S_b-L'+i; otherwise as pyr_score
+ *   kept_idx, out_offsets_dev, k_out, v_out: as in pyr_prefill_layer (out of place: k_out
+ *                      must not overlap k)
+ *   workspace          dev, >= pyr_decode_workspace_bytes(), 256-byte aligned
+ * Five launches on the stream: per-key-block softmax statistics of the window rows, their
+ * fold into row denominators, the score pass, the selection, the gathers.  The attention
+ * output of the new token itself is not computed here.
+ */
+PYR_API int pyr_decode_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out);
+PYR_API int pyr_decode_update(const void* q_win, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      const float* row_weights_dev, const int32_t* pos,
+                      float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, int32_t* pos_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

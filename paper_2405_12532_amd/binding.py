@@ -41,6 +41,9 @@ _SIGNATURES = {
     "pyr_gather_positions": (ctypes.c_int, [_VP, _VP, _I64, _VP, _VP]),
     "pyr_prefill_layer_ex": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                             _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
+    "pyr_decode_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(PyrShape), _I32, ctypes.POINTER(_SZ)]),
+    "pyr_decode_update": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
+                                         _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
     "pyr_prefill_layer": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                          _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
 }
@@ -165,6 +168,22 @@ def prefill_layer(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_
                                     int(workspace_bytes_), _stream(stream)), "pyr_prefill_layer")
 
 
+def decode_workspace_bytes(shape: PyrShape, w: int) -> int:
+    out = _SZ(0)
+    _check(load().pyr_decode_workspace_bytes(ctypes.byref(shape), int(w), ctypes.byref(out)), "pyr_decode_workspace_bytes")
+    return int(out.value)
+
+
+def decode_update(q_win, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev, keep_len_host,
+                  row_weights_dev, pos, scores, kept_idx, out_offsets_dev, k_out, v_out, pos_out, workspace,
+                  workspace_bytes_, stream=None):
+    _check(load().pyr_decode_update(_ptr(q_win), _ptr(k), _ptr(v), _ptr(seq_offsets_dev), _ptr(seq_offsets_host),
+                                    ctypes.byref(shape), int(w), float(softmax_scale), _ptr(keep_len_dev),
+                                    _ptr(keep_len_host), _ptr(row_weights_dev), _ptr(pos), _ptr(scores), _ptr(kept_idx),
+                                    _ptr(out_offsets_dev), _ptr(k_out), _ptr(v_out), _ptr(pos_out), _ptr(workspace),
+                                    int(workspace_bytes_), _stream(stream)), "pyr_decode_update")
+
+
 # ----------------------------------------------------------------------------- convenience for tests / smoke
 def to_device_bf16(bits_u16):
     """numpy uint16 bf16 bit patterns -> torch.bfloat16 tensor on the GPU (same bits)."""
@@ -226,4 +245,38 @@ def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0, row_weights=N
     res.update(out=to_host_bits(out), scores=scores.cpu().numpy(), kept_idx=kept.cpu().numpy()[:n_kept].astype(np.int64),
                out_offsets=out_off.cpu().numpy(), k_out=to_host_bits(k_out)[:n_kept], v_out=to_host_bits(v_out)[:n_kept],
                lse=ws[: T * Hq * 4].view(torch.float32).reshape(T, Hq).cpu().numpy())
+    return res
+
+
+def decode_update_from_numpy(q_win_bits, k_bits, v_bits, seq_offsets, keep_len, w, softmax_scale=0.0, row_weights=None,
+                             pos=None):
+    """Upload a compressed cache (bf16 bit patterns) and the window's queries, run pyr_decode_update, download."""
+    import numpy as np
+    import torch
+    q_win, k, v = (to_device_bf16(a) for a in (q_win_bits, k_bits, v_bits))
+    B, _, Hq, d = q_win.shape
+    T, Hkv = k.shape[0], k.shape[1]
+    off_h = torch.from_numpy(np.ascontiguousarray(seq_offsets, dtype=np.int32))
+    keep_h = torch.from_numpy(np.ascontiguousarray(keep_len, dtype=np.int32))
+    off_d, keep_d = off_h.cuda(), keep_h.cuda()
+    lens = np.diff(seq_offsets)
+    shape = make_shape(B, T, int(lens.max()) if B else 0, Hq, Hkv, d)
+    n_kept = int(keep_h.sum())
+    ws_bytes = decode_workspace_bytes(shape, w)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    scores = torch.empty(T, dtype=torch.float32, device="cuda")
+    kept = torch.empty(max(n_kept, 1), dtype=torch.int32, device="cuda")
+    out_off = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    k_out = torch.empty((max(n_kept, 1), Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.empty_like(k_out)
+    rw_d = None if row_weights is None else torch.from_numpy(np.ascontiguousarray(row_weights, dtype=np.float32)).cuda()
+    pos_d = None if pos is None else torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).cuda()
+    pos_out = None if pos is None else torch.empty(max(n_kept, 1), dtype=torch.int32, device="cuda")
+    decode_update(q_win, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, rw_d, pos_d, scores, kept, out_off,
+                  k_out, v_out, pos_out, ws, ws_bytes)
+    torch.cuda.synchronize()
+    res = dict(scores=scores.cpu().numpy(), kept_idx=kept.cpu().numpy()[:n_kept].astype(np.int64),
+               out_offsets=out_off.cpu().numpy(), k_out=to_host_bits(k_out)[:n_kept], v_out=to_host_bits(v_out)[:n_kept])
+    if pos is not None:
+        res["pos_out"] = pos_out.cpu().numpy()[:n_kept]
     return res

@@ -266,4 +266,62 @@ int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
     return rc;
 }
 
+int pyr_decode_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out) {
+    if (bytes_out == nullptr) return PYR_ERR_NULL;
+    const int rc = check_shape(shape);
+    if (rc != PYR_OK) return rc;
+    if (w < 1) return PYR_ERR_SHAPE;
+    *bytes_out = align_up((size_t)shape->n_seqs * w * shape->n_q_heads * sizeof(float)) +
+                 align_up(pyr::window_score_part_bytes(*shape, w));
+    return PYR_OK;
+}
+
+int pyr_decode_update(const void* q_win, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      const float* row_weights_dev, const int32_t* pos,
+                      float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, int32_t* pos_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != PYR_OK) return rc;
+    if (w < 1) return PYR_ERR_SHAPE;
+    if (!q_win || !k || !v || !scores || !kept_idx || !out_offsets_dev || !seq_offsets_dev || !seq_offsets_host ||
+        !keep_len_dev || !keep_len_host)
+        return PYR_ERR_NULL;
+    if ((k_out == nullptr) != (v_out == nullptr) || (pos == nullptr) != (pos_out == nullptr)) return PYR_ERR_NULL;
+    if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+        return PYR_ERR_UNSUPPORTED;
+    BatchInfo info;
+    rc = check_offsets(seq_offsets_host, shape->n_seqs, shape->total_tokens, shape->max_seqlen, &info);
+    if (rc != PYR_OK) return rc;
+    int64_t total_kept = 0;
+    rc = check_keep_len(keep_len_host, seq_offsets_host, shape->n_seqs, w, &total_kept);
+    if (rc != PYR_OK) return rc;
+    size_t need = 0;
+    rc = pyr_decode_workspace_bytes(shape, w, &need);
+    if (rc != PYR_OK) return rc;
+    if (workspace == nullptr || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return PYR_ERR_WORKSPACE;
+
+    float* lse_win = (float*)workspace;
+    void* part = (char*)workspace + align_up((size_t)shape->n_seqs * w * shape->n_q_heads * sizeof(float));
+    hipStream_t st = (hipStream_t)stream;
+    pyr_shape s = *shape;
+    s.max_seqlen = info.max_len;
+    rc = pyr::launch_window_score(q_win, k, seq_offsets_dev, s, w, scale_log2(softmax_scale, shape->head_dim),
+                                  row_weights_dev, lse_win, part, scores, st);
+    if (rc != PYR_OK) return rc;
+    rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
+                            out_offsets_dev, st);
+    if (rc != PYR_OK) return rc;
+    if (k_out != nullptr && total_kept > 0) {
+        const size_t row_bytes = (size_t)shape->n_kv_heads * shape->head_dim * 2;
+        rc = pyr::launch_gather(k, k_out, v, v_out, row_bytes, kept_idx, total_kept, st);
+        if (rc != PYR_OK) return rc;
+    }
+    if (pos != nullptr && total_kept > 0) rc = pyr::launch_gather_positions(pos, kept_idx, total_kept, pos_out, st);
+    return rc;
+}
+
 }  // extern "C"

@@ -37,6 +37,14 @@ int launch_score(const void* q, const void* k, const float* lse, const int32_t* 
                  const pyr_shape& shape, int32_t w, float scale_log2, const float* row_weights, float* scores,
                  hipStream_t stream);
 
+// Generation phase: the same scores from the window's own query buffer q_win [B, w, Hq, d]
+// (right-aligned), three launches: per-block row statistics -> part, folded into lse_win
+// [B, w, Hq], then the score pass.  part holds window_score_part_bytes() bytes.
+size_t window_score_part_bytes(const pyr_shape& shape, int32_t w);
+int launch_window_score(const void* q_win, const void* k, const int32_t* seq_offsets_dev, const pyr_shape& shape,
+                        int32_t w, float scale_log2, const float* row_weights, float* lse_win, void* part,
+                        float* scores, hipStream_t stream);
+
 int launch_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept, int32_t* pos_out,
                             hipStream_t stream);
 

@@ -25,12 +25,19 @@
 // (fully coalesced: 16 lanes per 256-byte row, 16-byte chunks XOR-swizzled against bank
 // conflicts), copies the fragments into registers and at once requests the next tile into
 // the same LDS space, which then arrives while the MFMAs and exponentials of this one run.
+//
+// The same walk serves the generation-phase update of the cache (Algorithm 1 with a non-empty
+// cache; Section 4.1): there the queries of the recent rows come in a buffer of their own
+// ([B, w, Hq, d], right-aligned) and no attention pass has left row denominators behind, so a
+// first pass (kStats) writes, per 64-key workgroup, every window row's maximum and sum of
+// exponentials, a small kernel folds them into denominators, and the score pass runs as above.
 #include "pyr_internal.h"
 
 namespace pyr {
 namespace {
 
 constexpr int kWavesPerBlock = 2;    // head groups
+enum Mode { kScores = 0, kScoresWeighted = 1, kStats = 2 };
 constexpr int kKeysPerBlock = 64;
 
 typedef __attribute__((address_space(3))) char* lptr_t;
@@ -56,18 +63,24 @@ __device__ __forceinline__ void wait_loads() {      // until at most N of this w
 }
 __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int D, bool kWeighted>
+// q_window == 0: q and lse are indexed by packed row like k ([T, Hq, d], [T, Hq]);
+// q_window != 0: by (sequence, window slot): [B, w, Hq, d], [B, w, Hq], the last row in slot w-1.
+// kStats writes part[((key block * B + b) * w + slot) * Hq + h] = (max, sum of 2^(x - max)) over the
+// block's visible keys, x = c * q.k, and touches neither lse nor scores.
+template <int D, int kMode>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
-    const int32_t* __restrict__ seq_offsets, int32_t n_q_heads, int32_t n_kv_heads, int32_t w, int32_t blocks_per_seq,
-    float c, const float* __restrict__ row_weights, float* __restrict__ scores) {
+    const int32_t* __restrict__ seq_offsets, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t w,
+    int32_t blocks_per_seq, int32_t q_window, float c, const float* __restrict__ row_weights,
+    float* __restrict__ scores, float2* __restrict__ part) {
+    constexpr bool kWeighted = kMode == kScoresWeighted;
     constexpr int kKSteps = D / 16;
     constexpr int kChunks = D / 8;                  // 16-byte chunks per row
     constexpr int kRowBytes = D * 2;
     constexpr int kRowsPerLoad = 64 / kChunks;      // rows one load instruction covers
     constexpr int kKBytes = 64 * kRowBytes, kQBytes = 32 * kRowBytes, kLseBytes = 256;
     constexpr int kNK = kKBytes / 1024, kNQ = kQBytes / 1024;       // load instructions per K tile, per Q tile
-    constexpr int kStepLoads = kNQ + (kWeighted ? 2 : 1);           // ... per step: Q tile, denominators, weights
+    constexpr int kStepLoads = kNQ + (kMode == kStats ? 0 : kWeighted ? 2 : 1);   // ... per step: Q tile, denominators, weights
     constexpr int kRedBytes = kWavesPerBlock * 2 * 64 * 17 * 4;     // +1 column: conflict-free column sums
     constexpr int kSmemBytes = kWavesPerBlock * (kKBytes + kQBytes + 2 * kLseBytes);
     static_assert(kSmemBytes >= kRedBytes, "the final reduction reuses the tiles' space");
@@ -82,6 +95,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     if (key_base >= S) return;                        // uniform over the workgroup
     const int L = min(w, S);
     const int first_row = S - L;                      // local position of the first window row
+    const int q_row_base = q_window ? b * w + (w - L) : row0 + first_row;   // row of q / lse holding the first window row
+    const int key_block = blockIdx.x % blocks_per_seq;
     const int n_row_blocks = (L + 31) / 32;
     const int group = n_q_heads / n_kv_heads;
     const int n_steps = group * n_row_blocks;         // per KV head
@@ -102,8 +117,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         for (int j = lane; j < L; j += 64) part += row_weights[w - L + j];
 #pragma unroll
         for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
-        weight_sum = part;
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(weight_sum) : : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(part) : : "memory");
+        weight_sum = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, part)));   // uniform: a scalar register
     }
 
     // ---- this wavefront's LDS: K tile, Q tile (1 KB aligned), then the row denominators
@@ -135,15 +150,16 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         const int rb_row0 = first_row + 32 * rb;
         int last_row = L - 1 - 32 * rb;
         asm volatile("" : "+v"(last_row));
-        const char* base = (const char*)(q + ((size_t)(row0 + rb_row0) * n_q_heads + h) * D);
+        const char* base = (const char*)(q + ((size_t)(q_row_base + 32 * rb) * n_q_heads + h) * D);
 #pragma unroll
         for (int i = 0; i < kNQ; ++i) {
             const int row = kRowsPerLoad * i + ld_row;
             lds_dma(base, (uint32_t)min(row, last_row) * q_row_bytes + 16 * (ld_chunk ^ (row & (kChunks - 1))),
                     qt + 1024 * i, false);
         }
-        lds_dma((const char*)(lse + (size_t)(row0 + rb_row0) * n_q_heads + h), (uint32_t)min(li, last_row) * n_q_heads * 4,
-                lt, true);
+        if (kMode != kStats)
+            lds_dma((const char*)(lse + (size_t)(q_row_base + 32 * rb) * n_q_heads + h),
+                    (uint32_t)min(li, last_row) * n_q_heads * 4, lt, true);
         if (kWeighted) lds_dma((const char*)(row_weights + (w - L) + 32 * rb), (uint32_t)min(li, last_row) * 4, wt, true);
     };
 
@@ -174,7 +190,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
             bf16x8 qf[kKSteps];
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = frag(qt, li, ks);
-            float lse_row = *(const float __attribute__((address_space(3)))*)(uintptr_t)(lt + 4 * li);
+            float lse_row = 0.f;
+            if (kMode != kStats) lse_row = *(const float __attribute__((address_space(3)))*)(uintptr_t)(lt + 4 * li);
             if (kWeighted)      // omega * 2^x = 2^(x + log2 omega); a zero weight gives 2^-inf = 0
                 lse_row -= __builtin_amdgcn_logf(*(const float __attribute__((address_space(3)))*)(uintptr_t)(wt + 4 * li));
             wait_lds();
@@ -186,6 +203,44 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
             if (first_row + 32 * rb + 31 < key_base) continue;      // whole row block precedes the keys
             // masks are only needed where the keys reach into the window or the row block is ragged
             const bool plain = key_base + 63 <= first_row + 32 * rb && first_row + 32 * rb + 31 < S;   // uniform
+            if (kMode == kStats) {
+                // this row's maximum and sum of exponentials over the 32 keys the lane holds, then
+                // over the 32 the other half-wavefront holds
+                f32x16 x[2];
+                float mx = -INFINITY;
+#pragma unroll
+                for (int sk = 0; sk < 2; ++sk) {
+                    f32x16 s;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < kKSteps; ++ks)
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sk][ks], qf[ks], s, 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key_base + 32 * sk + 8 * (r >> 2) + 4 * gl + (r & 3);
+                        const bool visible = plain || (key <= qpos && qpos < S);
+                        x[sk][r] = visible ? s[r] * c : -INFINITY;
+                        mx = fmaxf(mx, x[sk][r]);
+                    }
+                }
+                float sum = 0.f;
+                if (mx > -INFINITY) {
+#pragma unroll
+                    for (int sk = 0; sk < 2; ++sk)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(x[sk][r] - mx);
+                }
+                const float mo = __shfl_xor(mx, 32, 64), so = __shfl_xor(sum, 32, 64);
+                const float m_all = fmaxf(mx, mo);
+                if (gl == 0 && m_all > -INFINITY && 32 * rb + li < L) {
+                    const float total = (mx > -INFINITY ? sum * __builtin_amdgcn_exp2f(mx - m_all) : 0.f) +
+                                        (mo > -INFINITY ? so * __builtin_amdgcn_exp2f(mo - m_all) : 0.f);
+                    const int h = kvh * group + st / n_row_blocks, slot = (w - L) + 32 * rb + li;
+                    part[(((size_t)key_block * n_seqs + b) * w + slot) * n_q_heads + h] = make_float2(m_all, total);
+                }
+                continue;
+            }
 #pragma unroll
             for (int sk = 0; sk < 2; ++sk) {
                 f32x16 s;
@@ -210,6 +265,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         }
     }
     // every load issued above has been waited for: nothing is in flight towards LDS here
+    if (kMode == kStats) return;
 
     // ---- add the 32 window-row lanes of each half and the two head groups, fixed order
     const float norm = 1.0f / ((float)n_q_heads * weight_sum);
@@ -232,26 +288,90 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     }
 }
 
+// Row denominators of the window rows from the per-block statistics: for every (sequence,
+// window slot, head) fold (max, sum) over the key blocks the row can see, in block order:
+//   lse = M + log2(sum_kb sum_kb * 2^(m_kb - M)),  M = max_kb m_kb.
+__global__ __launch_bounds__(256) void fold_stats_kernel(const float2* __restrict__ part,
+                                                         const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
+                                                         int32_t n_q_heads, int32_t w, float* __restrict__ lse_win) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)n_seqs * w * n_q_heads) return;
+    const int slot = (int)((idx / n_q_heads) % w), b = (int)(idx / ((int64_t)n_q_heads * w));
+    const int S = seq_offsets[b + 1] - seq_offsets[b];
+    const int L = min(w, S), i = slot - (w - L);
+    if (i < 0) {                                      // slot not in use (sequence shorter than the window)
+        lse_win[idx] = 0.f;
+        return;
+    }
+    const int n_blocks = (S - L + i) / kKeysPerBlock + 1;        // key blocks row S-L+i can see
+    const size_t stride = (size_t)n_seqs * w * n_q_heads;
+    float m_run = -INFINITY, s_run = 0.f;
+    for (int kb = 0; kb < n_blocks; ++kb) {
+        const float2 p = part[kb * stride + idx];
+        if (p.x > m_run) {
+            s_run = s_run * __builtin_amdgcn_exp2f(m_run - p.x) + p.y;      // (2^-inf = 0 the first time)
+            m_run = p.x;
+        } else {
+            s_run += p.y * __builtin_amdgcn_exp2f(p.x - m_run);
+        }
+    }
+    lse_win[idx] = m_run + __builtin_amdgcn_logf(s_run);
+}
+
+}  // namespace
+
+namespace {
+template <int kMode>
+int launch_walk(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev, const pyr_shape& s,
+                int32_t w, int32_t q_window, float scale_log2, const float* row_weights, float* scores, float2* part,
+                hipStream_t stream) {
+    const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
+    const int64_t n_blocks = (int64_t)blocks_per_seq * s.n_seqs;
+    if (n_blocks >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)n_blocks, 1, 1), block(kWavesPerBlock * 64);
+    if (s.head_dim == 128)
+        hipLaunchKernelGGL((score_kernel<128, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, q_window, scale_log2,
+                           row_weights, scores, part);
+    else
+        hipLaunchKernelGGL((score_kernel<64, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, q_window, scale_log2,
+                           row_weights, scores, part);
+    return check_launch();
+}
 }  // namespace
 
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
                  const pyr_shape& s, int32_t w, float scale_log2, const float* row_weights, float* scores,
                  hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
-    const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
-    const int64_t n_blocks = (int64_t)blocks_per_seq * s.n_seqs;
-    if (n_blocks >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
-    dim3 grid((unsigned)n_blocks, 1, 1), block(kWavesPerBlock * 64);
-    auto launch = [&](auto kern) {
-        hipLaunchKernelGGL(kern, grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse, seq_offsets_dev,
-                           s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, scale_log2, row_weights, scores);
-    };
-    if (s.head_dim == 128) {
-        if (row_weights) launch(score_kernel<128, true>); else launch(score_kernel<128, false>);
-    } else {
-        if (row_weights) launch(score_kernel<64, true>); else launch(score_kernel<64, false>);
-    }
-    return check_launch();
+    return row_weights ? launch_walk<kScoresWeighted>(q, k, lse, seq_offsets_dev, s, w, 0, scale_log2, row_weights, scores,
+                                                      nullptr, stream)
+                       : launch_walk<kScores>(q, k, lse, seq_offsets_dev, s, w, 0, scale_log2, nullptr, scores, nullptr,
+                                              stream);
+}
+
+size_t window_score_part_bytes(const pyr_shape& s, int32_t w) {
+    const size_t blocks_per_seq = ((size_t)s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
+    return blocks_per_seq * (size_t)s.n_seqs * (size_t)w * (size_t)s.n_q_heads * sizeof(float2);
+}
+
+int launch_window_score(const void* q_win, const void* k, const int32_t* seq_offsets_dev, const pyr_shape& s, int32_t w,
+                        float scale_log2, const float* row_weights, float* lse_win, void* part, float* scores,
+                        hipStream_t stream) {
+    if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
+    int rc = launch_walk<kStats>(q_win, k, nullptr, seq_offsets_dev, s, w, 1, scale_log2, nullptr, nullptr, (float2*)part,
+                                 stream);
+    if (rc != PYR_OK) return rc;
+    const int64_t n = (int64_t)s.n_seqs * w * s.n_q_heads;
+    if ((n + 255) / 256 >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(fold_stats_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const float2*)part,
+                       seq_offsets_dev, s.n_seqs, s.n_q_heads, w, lse_win);
+    if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
+    return row_weights ? launch_walk<kScoresWeighted>(q_win, k, lse_win, seq_offsets_dev, s, w, 1, scale_log2, row_weights,
+                                                      scores, nullptr, stream)
+                       : launch_walk<kScores>(q_win, k, lse_win, seq_offsets_dev, s, w, 1, scale_log2, nullptr, scores,
+                                              nullptr, stream);
 }
 
 }  // namespace pyr

@@ -147,3 +147,25 @@ def test_position_and_weight_entry_points_reject_bad_arguments():
                                   0x5000, None) == -1
     assert lib.pyr_score_weighted(0x1000, 0x2000, 0x6000, 0x3000, off.data_ptr(), ctypes.byref(shape), 0, 0.0, 0x4000,
                                   0x5000, None) == -2
+
+
+def test_decode_update_rejects_bad_arguments_before_launching():
+    lib = binding.load()
+    shape = binding.make_shape(2, 30, 20, 4, 2, 64)
+    n = binding.decode_workspace_bytes(shape, 4)
+    assert n % 256 == 0 and n >= 2 * 4 * 4 * 4 + 1 * 2 * 4 * 4 * 8        # denominators + one key block of statistics
+    off, keep = Host([0, 10, 30]), Host([6, 12])
+
+    def call(q_win=0x10000, offsets=off, keeps=keep, w=4, ws=0x40000, ws_bytes=1 << 20, pos=None, pos_out=None, v_out=0xC0000):
+        return lib.pyr_decode_update(q_win, 0x20000, 0x30000, 0x50000, offsets.data_ptr(), ctypes.byref(shape), w, 0.0,
+                                     0x60000, keeps.data_ptr(), None, pos, 0x80000, 0x90000, 0xA0000, 0xB0000, v_out,
+                                     pos_out, ws, ws_bytes, None)
+    assert call(q_win=None) == -1
+    assert call(q_win=0x10008) == -3
+    assert call(offsets=Host([0, 12, 11])) == -5
+    assert call(keeps=Host([3, 12])) == -4                                   # below the window
+    assert call(w=0) == -2
+    assert call(ws_bytes=64) == -6
+    assert call(ws=0x40010) == -6
+    assert call(pos=0xE0000) == -1                                           # ids in but nowhere to put them
+    assert call(v_out=None) == -1

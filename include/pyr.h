@@ -82,6 +82,21 @@ PYR_API int pyr_schedule_next(int32_t S, int32_t w, int32_t num, int32_t den, in
                       int32_t* keep_len_out);
 
 /*
+ * Host only.  Lengths of one sequence through n_layers layers, each with its own ratio
+ * num[l]/den and minimum PvC length floor_len[l] (Algorithm 1: input N = {N_0, ...} and a p
+ * that decays from layer to layer - the caller chooses the sequence p_l, e.g. geometric or
+ * one of the patterns of the decay ablation in Section 5):
+ *   context_relative == 0:  k = floor((num[l]*S + den/2)/den)                 (as pyr_schedule_next)
+ *   context_relative != 0:  k = L' + floor((num[l]*(S-L') + den/2)/den), L' = min(w,S)
+ *                           (Algorithm 1 ranks the columns :-L only: p as a fraction of the context)
+ * then k = max(k, floor_len[l], L') capped at S, and S <- k.
+ *   len_out            host int32 [n_layers+1], written: len_out[0] = S, len_out[l+1] after layer l
+ * Errors: PYR_ERR_NULL, PYR_ERR_SHAPE (as pyr_schedule_next, per layer; len_out is then partly written).
+ */
+PYR_API int pyr_schedule_plan(int32_t S, int32_t w, int32_t n_layers, const int32_t* num, int32_t den,
+                      const int32_t* floor_len, int32_t context_relative, int32_t* len_out);
+
+/*
  * Step 1 - attention weights applied to V (Algorithm 1, "compute attention
  * weights of KV"): causal softmax attention inside each sequence,
  *   out[i,h,:] = sum_{j<=i} softmax_j(scale * q[i,h,:].k[j,h/g,:]) v[j,h/g,:].

@@ -56,6 +56,7 @@ __all__ = [
     "gather_rows",
     "gather_positions",
     "schedule_next",
+    "schedule_plan",
     "prefill_layer",
     "decode_update",
 ]
@@ -196,6 +197,35 @@ def schedule_next(S, w, num, den, floor_len):
     k = (num * S + den // 2) // den
     k = max(k, floor_len, min(w, S))
     return min(k, S)
+
+
+def schedule_plan(S, w, nums, den, floors, context_relative=False):
+    """Lengths of one sequence through a stack of layers: [S_0, S_1, ..., S_n].
+
+    Algorithm 1 with a ratio and a minimum PvC length of its own per layer (input N = {N_0, ..., N_l, ...};
+    "reduce p by multiplying a decay ratio", so p_l is whatever sequence the caller chose: geometric, or the
+    patterns of the decay ablation of Section 5).  Layer l keeps
+        whole-length reading:   k = round_half_up(p_l * S_l)
+        context reading:        k = L' + round_half_up(p_l * (S_l - L')),  L' = min(w, S_l)
+    (Algorithm 1 ranks only the columns :-L, so read literally p is a fraction of the context), then
+    k = max(k, N_l, L') capped at S_l, and S_{l+1} = k.
+    """
+    S, w, den = int(S), int(w), int(den)
+    if len(nums) != len(floors):
+        raise ValueError("one ratio and one minimum length per layer")
+    out = [S]
+    for num, floor_len in zip(nums, floors):
+        num, floor_len = int(num), int(floor_len)
+        if context_relative:
+            if S < 0 or w < 1 or den <= 0 or num < 0 or num > den or floor_len < 0:
+                raise ValueError("bad schedule arguments")
+            L = min(w, S)
+            k = L + (num * (S - L) + den // 2) // den
+            S = min(max(k, floor_len, L), S)
+        else:
+            S = schedule_next(S, w, num, den, floor_len)
+        out.append(S)
+    return out
 
 
 def prefill_layer(q, k, v, seq_offsets, w, keep_len, scale=None, hidden=None, out_rows=None, row_weights=None,

@@ -32,6 +32,8 @@ _SIGNATURES = {
     "pyr_version": (ctypes.c_int, []),
     "pyr_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(PyrShape), _I32, ctypes.POINTER(_SZ)]),
     "pyr_schedule_next": (ctypes.c_int, [_I32, _I32, _I32, _I32, _I32, ctypes.POINTER(_I32)]),
+    "pyr_schedule_plan": (ctypes.c_int, [_I32, _I32, _I32, ctypes.POINTER(_I32), _I32, ctypes.POINTER(_I32), _I32,
+                                         ctypes.POINTER(_I32)]),
     "pyr_attention": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _F32, _VP, _VP, _VP, _VP]),
     "pyr_score": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP]),
     "pyr_score_weighted": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP, _VP]),
@@ -106,6 +108,16 @@ def schedule_next(S: int, w: int, num: int, den: int, floor_len: int) -> int:
     _check(load().pyr_schedule_next(int(S), int(w), int(num), int(den), int(floor_len), ctypes.byref(out)),
            "pyr_schedule_next")
     return int(out.value)
+
+
+def schedule_plan(S: int, w: int, nums, den: int, floors, context_relative: bool = False):
+    n = len(nums)
+    if len(floors) != n:
+        raise ValueError("one ratio and one minimum length per layer")
+    num_a, floor_a, out = (_I32 * max(n, 1))(*nums), (_I32 * max(n, 1))(*floors), (_I32 * (n + 1))()
+    _check(load().pyr_schedule_plan(int(S), int(w), n, num_a, int(den), floor_a, int(bool(context_relative)), out),
+           "pyr_schedule_plan")
+    return list(out)
 
 
 def attention(q, k, v, seq_offsets_dev, seq_offsets_host, shape, softmax_scale, out, lse, tile_map, stream=None):

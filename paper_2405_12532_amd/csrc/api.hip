@@ -112,6 +112,25 @@ int pyr_schedule_next(int32_t S, int32_t w, int32_t num, int32_t den, int32_t fl
     return PYR_OK;
 }
 
+int pyr_schedule_plan(int32_t S, int32_t w, int32_t n_layers, const int32_t* num, int32_t den, const int32_t* floor_len,
+                      int32_t context_relative, int32_t* len_out) {
+    if (len_out == nullptr || (n_layers > 0 && (num == nullptr || floor_len == nullptr))) return PYR_ERR_NULL;
+    if (S < 0 || w < 1 || den <= 0 || n_layers < 0) return PYR_ERR_SHAPE;
+    len_out[0] = S;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (num[l] < 0 || num[l] > den || floor_len[l] < 0) return PYR_ERR_SHAPE;
+        const int64_t recent = w < S ? w : S;
+        int64_t k = context_relative ? recent + ((int64_t)num[l] * (S - recent) + den / 2) / den
+                                     : ((int64_t)num[l] * S + den / 2) / den;
+        if (k < floor_len[l]) k = floor_len[l];
+        if (k < recent) k = recent;
+        if (k > S) k = S;
+        S = (int32_t)k;
+        len_out[l + 1] = S;
+    }
+    return PYR_OK;
+}
+
 int pyr_attention(const void* q, const void* k, const void* v,
                   const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
                   const pyr_shape* shape, float softmax_scale,

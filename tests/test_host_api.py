@@ -169,3 +169,20 @@ def test_decode_update_rejects_bad_arguments_before_launching():
     assert call(ws=0x40010) == -6
     assert call(pos=0xE0000) == -1                                           # ids in but nowhere to put them
     assert call(v_out=None) == -1
+
+
+def test_schedule_plan_matches_oracle():
+    rng = np.random.default_rng(80)
+    for _ in range(300):
+        S0, w, den = int(rng.integers(0, 40000)), int(rng.integers(1, 300)), int(rng.integers(1, 1000))
+        n = int(rng.integers(0, 40))
+        nums, floors = rng.integers(0, den + 1, n).tolist(), rng.integers(0, 400, n).tolist()
+        for ctx in (False, True):
+            assert binding.schedule_plan(S0, w, nums, den, floors, ctx) == orc.schedule_plan(S0, w, nums, den, floors, ctx)
+    golden = [int(x) for x in open(os.path.join(ROOT, "tests", "golden", "pyramid_lengths_2048_093_192.txt"))
+              .read().split("#")[0].split()]
+    assert binding.schedule_plan(2048, 64, [93] * 32, 100, [192] * 32) == golden
+    for bad in [(-1, 4, [1], 2, [0]), (10, 0, [1], 2, [0]), (10, 4, [3], 2, [0]), (10, 4, [1], 0, [0]), (10, 4, [1], 2, [-1])]:
+        with pytest.raises(binding.PyrError) as e:
+            binding.schedule_plan(*bad)
+        assert e.value.status == -2

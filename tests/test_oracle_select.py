@@ -295,3 +295,40 @@ def test_decode_update_fixed_budget_over_many_steps():
         k, v, pos = r["k_out"], r["v_out"], r["pos_out"]
         assert k.shape[0] == min(S, budget)
         assert pos[-w:].tolist() == list(range(step - w + 1, step + 1)) and np.all(np.diff(pos) > 0)
+
+
+# ---- per-layer ratios and minimum lengths (Algorithm 1: N = {N_0, ...}, decaying p)
+
+def test_schedule_plan_against_rational_arithmetic_and_golden():
+    golden = [int(t) for t in open(os.path.join(os.path.dirname(__file__), "golden", "pyramid_lengths_2048_093_192.txt"))
+              .read().split("#")[0].split()]
+    assert orc.schedule_plan(2048, 64, [93] * 32, 100, [192] * 32) == golden
+    rng = np.random.default_rng(70)
+    for _ in range(200):
+        S0, w, den = int(rng.integers(0, 5000)), int(rng.integers(1, 200)), int(rng.integers(1, 1000))
+        n = int(rng.integers(1, 12))
+        nums, floors = rng.integers(0, den + 1, n).tolist(), rng.integers(0, 300, n).tolist()
+        for ctx in (False, True):
+            got = orc.schedule_plan(S0, w, nums, den, floors, context_relative=ctx)
+            S = S0
+            for l in range(n):
+                L = min(w, S)
+                base = (S - L) if ctx else S
+                k = (L if ctx else 0) + int(math.floor(Fraction(nums[l] * base, den) + Fraction(1, 2)))
+                S = min(max(k, floors[l], L), S)
+                assert got[l + 1] == S
+            assert all(a >= b for a, b in zip(got, got[1:]))          # never grows
+
+
+def test_schedule_plan_closed_forms():
+    # p = 1 keeps everything; p = 0 keeps the window (or the floor); the context reading never drops the window
+    assert orc.schedule_plan(1000, 64, [10] * 5, 10, [0] * 5, context_relative=True) == [1000] * 6
+    assert orc.schedule_plan(1000, 64, [0, 0], 10, [0, 100], context_relative=True) == [1000, 64, 64]
+    assert orc.schedule_plan(1000, 64, [0], 10, [100], context_relative=True) == [1000, 100]
+    # half of the context of 1000 - 64 rows, then half of what is left: 64 + 468, 64 + 234
+    assert orc.schedule_plan(1000, 64, [1, 1], 2, [0, 0], context_relative=True) == [1000, 532, 298]
+    # geometric decay of p (0.8, 0.64, 0.512 of the context) written as the caller would
+    nums = [800, 640, 512]
+    assert orc.schedule_plan(2048, 48, nums, 1000, [0] * 3, context_relative=True) == [2048, 1648, 1072, 572]
+    with pytest.raises(ValueError):
+        orc.schedule_plan(10, 4, [1, 2], 2, [0])

@@ -671,17 +671,33 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     auto epilogue = [&]() __attribute__((always_inline)) {
         const float ltot = sum_with_other_half(l_run);
         const float inv = 1.0f / ltot;
+        // A lane holds 4 consecutive head-dim values of its row per accumulator quad (those of the
+        // other half-wavefront's lane follow them).  Stores cost the vector memory path one slot
+        // per lane whatever their width, so two quads are traded with the partner lane first: every
+        // lane then owns 8 consecutive values and stores 16 bytes.
+        u32x4 o16[kDTiles][2];
+#pragma unroll
+        for (int dt = 0; dt < kDTiles; ++dt)
+#pragma unroll
+            for (int ap = 0; ap < 2; ++ap) {
+                uint32_t lo[2], hi[2];              // quads a = 2*ap and a = 2*ap + 1, two packed pairs each
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    lo[e] = pack_bf16(oacc[dt][8 * ap + 2 * e] * inv, oacc[dt][8 * ap + 2 * e + 1] * inv);
+                    hi[e] = pack_bf16(oacc[dt][8 * ap + 4 + 2 * e] * inv, oacc[dt][8 * ap + 4 + 2 * e + 1] * inv);
+                    // afterwards lanes 0..31 hold their own quad 2*ap and the partner's, lanes 32..63 the
+                    // partner's quad 2*ap + 1 and their own
+                    auto r = __builtin_amdgcn_permlane32_swap(lo[e], hi[e], false, false);
+                    o16[dt][ap][e] = r[0];
+                    o16[dt][ap][2 + e] = r[1];
+                }
+            }
         if (qrow < cs.S) {
-            uint16_t* dst = out + ((size_t)(cs.row0 + qrow) * n_q_heads + cs.h) * D + 4 * gl;
+            uint16_t* dst = out + ((size_t)(cs.row0 + qrow) * n_q_heads + cs.h) * D + 8 * gl;
 #pragma unroll
             for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    bf16x4 o4;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][4 * a + e] * inv);
-                    *(bf16x4*)(dst + 32 * dt + 8 * a) = o4;
-                }
+                for (int ap = 0; ap < 2; ++ap) *(u32x4*)(dst + 32 * dt + 16 * ap) = o16[dt][ap];
             if (lse != nullptr && gl == 0)
                 lse[(size_t)(cs.row0 + qrow) * n_q_heads + cs.h] = m_run * c + __builtin_amdgcn_logf(ltot);
         }

@@ -70,7 +70,8 @@ struct Tile {
     static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
     static constexpr int kRowBytes = D * 2;
     static constexpr int kMatBytes = kBN * kRowBytes;           // one K or V tile
-    static constexpr size_t kLdsBytes = 2 * (size_t)kRing * kMatBytes;
+    static constexpr int kQStageBytes = 32 * kRowBytes / 2;     // half of a wavefront's 32 query rows
+    static constexpr size_t kLdsBytes = 2 * (size_t)kRing * kMatBytes + (size_t)kNW * kQStageBytes;
 };
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -373,29 +374,6 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         H = qlo / 32 + 1;
         n_my = qlo < sg.S ? (H + 1) / 2 : 0;
     };
-    // The query fragments are requested in assembly: the compiler's wait counter must not see
-    // these loads, or it would wait for every K/V load requested after them as well.  They are
-    // older than the K/V loads of the same stream position, so the wait that lets only the
-    // youngest position's loads stay in flight (wait_q, and every `top`) covers them.
-    auto load_q = [&](const Segment& sg) __attribute__((always_inline)) {
-        const int row = min(sg.q_base + 32 * rb + li, sg.S - 1);
-        const uint16_t* src = q + ((size_t)(sg.row0 + row) * n_q_heads + sg.h) * D + 8 * gl;
-#pragma unroll
-        for (int ks = 0; ks < NS; ++ks)
-            asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(qf[ks]) : "v"(src + 16 * ks) : "memory");
-    };
-    auto wait_q = [&]() __attribute__((always_inline)) {
-        if (NS == 8)
-            asm volatile("s_waitcnt vmcnt(%8)"
-                         : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[NS - 4]), "+v"(qf[NS - 3]),
-                           "+v"(qf[NS - 2]), "+v"(qf[NS - 1])
-                         : "n"(2 * kInstrPerWave) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(%4)"
-                         : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3])
-                         : "n"(2 * kInstrPerWave) : "memory");
-    };
-
     // ---- the workgroup's stream of key tiles
     Walker nx;                                    // walks the list of segments one ahead of the arithmetic
     nx.item = blockIdx.x / xcds;
@@ -451,9 +429,55 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     // a step apart: while one is between groups (checks, cursor arithmetic, the barrier itself)
     // the other one feeds the matrix pipe.
     const bool early_sync = wave >= kNW / 2;
+
+    // ---- query fragments.  Loads into registers pass the vector memory path at a quarter of the
+    // rate of loads that write LDS, and eight of them per wavefront at every change of segment held
+    // up the K/V loads of the whole workgroup.  The 32 query rows of a wavefront therefore come
+    // through a private LDS area of half their size, in two halves of the head dimension:
+    //   half 0 of the NEXT segment is requested as soon as a segment starts (the area is free then),
+    //   copied into registers once the current segment's last QK^T has been issued (q_turn), and
+    //   half 1 is requested into the same area at that moment and copied when the next segment starts.
+    // Rows are fetched 16 bytes per lane, 8 (4) lanes per 128-byte (64-byte) half row, chunks
+    // XOR-swizzled by row like the K tile.
+    constexpr int kQChunks = D / 16;                            // 16-byte chunks per half row
+    constexpr int kQRowsPerInstr = 64 / kQChunks;
+    constexpr int kQInstr = 32 / kQRowsPerInstr;                // load instructions per half
+    const uint32_t qstage = lds_base + 2 * kRing * T::kMatBytes + wave * T::kQStageBytes;
+    const int qs_row = lane / kQChunks, qs_chunk = lane % kQChunks;
+    auto q_request = [&](const Segment& sg, int half) __attribute__((always_inline)) {
+        const int first = min(sg.q_base + 32 * rb, sg.S - 1);   // rows past the end re-read the last row
+        const char* base = (const char*)(q + ((size_t)(sg.row0 + first) * n_q_heads + sg.h) * D);
+#pragma unroll
+        for (int i = 0; i < kQInstr; ++i) {
+            const int row = kQRowsPerInstr * i + qs_row;
+            const uint32_t voff = (uint32_t)min(row, sg.S - 1 - first) * ((uint32_t)n_q_heads * D * 2) +
+                                  (((qs_chunk ^ (row & (kQChunks - 1))) + half * kQChunks) << 4);
+            lds_dma16(base, voff, qstage + 1024 * i);
+        }
+    };
+    auto q_copy = [&](int half) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NS / 2; ++j) {
+            const int a = (int)qstage + ((li * kQChunks + ((2 * j + gl) ^ (li & (kQChunks - 1)))) << 4);
+            qf[half * (NS / 2) + j] = *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // in registers: the area may be overwritten
+    };
+    // once the current segment's last QK^T has been issued: half 0 into registers, request half 1
+    auto q_turn = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // (half 0 may be the youngest load of a very short segment)
+        q_copy(0);
+        q_request(nx.seg, 1);
+    };
+    // at the start of a segment: half 1 has landed (a whole stream position was requested after it)
+    auto wait_q = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kInstrPerWave) : "memory");
+        q_copy(1);
+        if (has_next) q_request(nx.seg, 0);
+    };
     auto sync = [&](bool with_q) __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * kInstrPerWave) : "memory");
-        if (with_q && has_next) load_q(nx.seg);
+        if (with_q && has_next) q_turn();
     };
 
     // ---- slices.  Everything below is written in the order it should be issued; a scheduling
@@ -704,7 +728,10 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     };
 
     // ---- the walk
-    load_q(cs);
+    q_request(cs, 0);                             // the first segment's queries: both halves one after the other
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    q_copy(0);
+    q_request(cs, 1);
     // K(0), K(1), V(0) first, then two more positions; wait for the first three
 #pragma unroll
     for (int i = 0; i < kInstrPerWave; ++i) load_piece(kp, 0, 0, i);

@@ -9,11 +9,15 @@
 // fixed stride.  The 32-row blocks are dealt to the wavefronts so that the two wavefronts of a
 // SIMD own blocks b and 7-b: every SIMD gets the same amount of causal work per segment.
 //
-// Keys/values stream through LDS in tiles of 64 positions in rings of three tiles each,
+// Keys/values stream through LDS in tiles of 64 positions in rings of four tiles each,
 // written by the load unit itself (global_load ... lds), so they never pass through
-// registers.  The tiles of all segments of a workgroup form ONE stream: the loads run three
-// (K) and one (V) stream positions ahead of the arithmetic, across segment boundaries, so
-// the compute unit never drains between segments.
+// registers.  The tiles of all segments of a workgroup form ONE stream: the loads run ahead
+// of the arithmetic across segment boundaries, so the compute unit never drains between
+// segments.  The query rows take the same road (a small private LDS area per wavefront, in
+// two halves) because loads into registers cost the vector memory path four times as much
+// and, issued by eight wavefronts at once, used to hold up the K/V stream at every change of
+// segment; for the same reason the output is stored 16 bytes per lane after a quad exchange
+// between the two halves of the wavefront.
 //
 // MFMA mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts).  The kernel computes the
 // TRANSPOSED logits  S^T = K Q^T  (keys x queries): in the accumulator layout a lane then
@@ -33,8 +37,9 @@
 //     QK0(t+1) | E1a(t)      PV0(t) | E1b(t)      QK1(t+1) | E0a(t+1)      PV1(t) | E0b(t+1)
 // A matrix instruction keeps the matrix pipe busy for 32 cycles but occupies the issue port
 // for about 10; the vector work of one slice (one FMA, one exponential, one add, half a
-// convert per logit pair) fits in the remainder, so one wavefront alone nearly saturates the
-// matrix pipe and the second wavefront of the SIMD covers what is left (barriers, waits).
+// convert per logit pair) fits in the remainder; the second wavefront of the SIMD, kept half a
+// step apart, covers the rest (barriers, waits, cursor arithmetic).  The sum and the bf16
+// pack of an exponential are issued one slice after it, so no slice waits on a transcendental.
 // Scheduling barriers after every slice pin this order.
 //
 // Numerics: bf16 products, fp32 accumulation, fp32 online softmax in base 2 with the scale

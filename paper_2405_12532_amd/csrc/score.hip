@@ -65,7 +65,7 @@ __device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)"
 
 // q_window == 0: q and lse are indexed by packed row like k ([T, Hq, d], [T, Hq]);
 // q_window != 0: by (sequence, window slot): [B, w, Hq, d], [B, w, Hq], the last row in slot w-1.
-// kStats writes part[((key block * B + b) * w + slot) * Hq + h] = (max, sum of 2^(x - max)) over the
+// kStats writes part[((key block * B + b) * Hq + h) * w + slot] = (max, sum of 2^(x - max)) over the
 // block's visible keys, x = c * q.k, and touches neither lse nor scores.
 template <int D, int kMode>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
                     const float total = (mx > -INFINITY ? sum * __builtin_amdgcn_exp2f(mx - m_all) : 0.f) +
                                         (mo > -INFINITY ? so * __builtin_amdgcn_exp2f(mo - m_all) : 0.f);
                     const int h = kvh * group + st / n_row_blocks, slot = (w - L) + 32 * rb + li;
-                    part[(((size_t)key_block * n_seqs + b) * w + slot) * n_q_heads + h] = make_float2(m_all, total);
+                    part[(((size_t)key_block * n_seqs + b) * n_q_heads + h) * w + slot] = make_float2(m_all, total);   // 32 rows: 256 consecutive bytes
                 }
                 continue;
             }
@@ -294,13 +294,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 __global__ __launch_bounds__(256) void fold_stats_kernel(const float2* __restrict__ part,
                                                          const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
                                                          int32_t n_q_heads, int32_t w, float* __restrict__ lse_win) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;        // (b, h, slot), slot fastest, as in part
     if (idx >= (int64_t)n_seqs * w * n_q_heads) return;
-    const int slot = (int)((idx / n_q_heads) % w), b = (int)(idx / ((int64_t)n_q_heads * w));
+    const int slot = (int)(idx % w), h = (int)((idx / w) % n_q_heads), b = (int)(idx / ((int64_t)n_q_heads * w));
+    float* dst = lse_win + ((size_t)b * w + slot) * n_q_heads + h;
     const int S = seq_offsets[b + 1] - seq_offsets[b];
     const int L = min(w, S), i = slot - (w - L);
     if (i < 0) {                                      // slot not in use (sequence shorter than the window)
-        lse_win[idx] = 0.f;
+        *dst = 0.f;
         return;
     }
     const int n_blocks = (S - L + i) / kKeysPerBlock + 1;        // key blocks row S-L+i can see
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(256) void fold_stats_kernel(const float2* __restric
             s_run += p.y * __builtin_amdgcn_exp2f(p.x - m_run);
         }
     }
-    lse_win[idx] = m_run + __builtin_amdgcn_logf(s_run);
+    *dst = m_run + __builtin_amdgcn_logf(s_run);
 }
 
 }  // namespace

@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # this script, scaled by what the same counters read for the hidden-row gather (a plain copy of known
 # size); the counter summary is profiles/layer_step_64x2k_pmc.txt.
 MEASURED_TRAFFIC = {
-    ("64x2k", "attention"): 6.45e9,       # 5.23 GB read + 1.22 GB written (algorithmic 4.31 GB)
+    ("64x2k", "attention"): 6.55e9,       # 5.34 GB read + 1.21 GB written (algorithmic 4.31 GB)
     ("64x2k", "gather"): 5.99e9,          # read = written = algorithmic after calibration
 }
 

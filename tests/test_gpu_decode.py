@@ -120,3 +120,9 @@ def test_decode_fixed_budget_generation(lib):
             Lb = min(w, lens[b])
             assert pos[b][-Lb:].tolist() == list(range(nxt[b] - Lb, nxt[b]))   # the window is the newest tokens
     print(f"[decode generation] 24 steps, budget {budget}: cache sizes {[a.shape[0] for a in k]}")
+
+
+def test_decode_update_with_empty_sequences(lib):
+    wl = synth.shrunk(synth.workload("cfg2"), (0, 130, 0, 9, 0), n_q_heads=4, n_kv_heads=2, head_dim=128, w=32,
+                      hidden_dim=0)
+    run_and_check(lib, wl, with_pos=True)

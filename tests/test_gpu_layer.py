@@ -180,3 +180,25 @@ def test_positions_follow_kept_rows(lib):
     res, ref, _ = run_and_check(lib, wl, pos=pos)
     if np.array_equal(res["kept_idx"], ref["kept_idx"]):
         assert np.array_equal(res["pos_out"], ref["pos_out"])
+
+
+# --------------------------------------------------------------------------- empty sequences, empty batch
+def test_empty_sequences_inside_a_batch(lib):
+    """Zero-length sequences at the start, in the middle and at the end of a ragged batch."""
+    wl = synth.shrunk(synth.workload("cfg2"), (0, 300, 0, 0, 5, 70, 0), n_q_heads=4, n_kv_heads=2, head_dim=64, w=16,
+                      hidden_dim=64)
+    res, ref, x = run_and_check(lib, wl, pos=np.arange(375, dtype=np.int32))
+    assert res["out_offsets"][1] == 0 and res["out_offsets"][-1] == int(x["keep_len"].sum())
+
+
+def test_empty_batch_launches_nothing(lib):
+    shape = lib.make_shape(0, 0, 0, 4, 2, 64)
+    off_h = torch.zeros(1, dtype=torch.int32)
+    keep_h = torch.zeros(1, dtype=torch.int32)                       # (no entries are read; the pointer must not be NULL)
+    dummy = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    ints = torch.full((4,), 7, dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(lib.workspace_bytes(shape, 16), 256), dtype=torch.uint8, device="cuda")
+    lib.prefill_layer(dummy, dummy, dummy, off_h.cuda(), off_h, shape, 16, 0.0, ints, keep_h, dummy, dummy.float(), ints,
+                      ints, dummy, dummy, ws, ws.numel())
+    torch.cuda.synchronize()
+    assert ints.cpu().tolist() == [7, 7, 7, 7]                       # nothing was written

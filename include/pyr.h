@@ -155,6 +155,8 @@ PYR_API int pyr_score_weighted(const void* q, const void* k, const float* lse,
  *   keep_len_dev       dev int32 [B];  keep_len_host  host copy, min(w,S_b) <= k_b <= S_b
  *   kept_idx           dev int32 [sum k_b], written: global packed row numbers
  *   out_offsets_dev    dev int32 [B+1], written: prefix sums of keep_len
+ * A sequence of length 0 (keep_len 0) contributes nothing; with n_seqs == 0 nothing is launched
+ * and nothing is written, out_offsets_dev[0] included.
  */
 PYR_API int pyr_select(const float* scores,
                const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,

@@ -186,3 +186,11 @@ def test_schedule_plan_matches_oracle():
         with pytest.raises(binding.PyrError) as e:
             binding.schedule_plan(*bad)
         assert e.value.status == -2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)

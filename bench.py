@@ -53,11 +53,13 @@ def cpu_baseline(wl, n_seqs_sample):
     from paper_2405_12532_amd import synth
     sub = synth.shrunk(wl, wl.seq_lens[:n_seqs_sample])
     x = synth.make_inputs(sub)
+    num, den, floor = sub.schedule_args()
+    keep = np.asarray([orc.schedule_next(S, sub.w, num, den, floor) for S in sub.seq_lens], dtype=np.int32)
     f = synth.bf16_bits_to_f64
     q, k, v = f(x["q"]), f(x["k"]), f(x["v"])
     hid = x.get("hidden")
     t0 = time.perf_counter()
-    orc.prefill_layer(q, k, v, x["seq_offsets"], sub.w, x["keep_len"], hidden=hid)
+    orc.prefill_layer(q, k, v, x["seq_offsets"], sub.w, keep, hidden=hid)
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
@@ -97,7 +99,8 @@ def main():
     q, k, v = (pyr.to_device_bf16(x[n]) for n in ("q", "k", "v"))
     hidden = pyr.to_device_bf16(x["hidden"]) if D > 0 else None
     off_h = torch.from_numpy(np.ascontiguousarray(x["seq_offsets"], dtype=np.int32))
-    keep_h = torch.from_numpy(np.ascontiguousarray(x["keep_len"], dtype=np.int32))
+    num, den, floor = wl.schedule_args()       # the retention rule of the workload, evaluated by the library's schedule
+    keep_h = torch.tensor([pyr.schedule_next(S, wl.w, num, den, floor) for S in wl.seq_lens], dtype=torch.int32)
     off_d, keep_d = off_h.cuda(), keep_h.cuda()
     n_kept = int(keep_h.sum())
     shape = pyr.make_shape(wl.n_seqs, T, max(wl.seq_lens), Hq, Hkv, d)

@@ -67,16 +67,13 @@ class Workload:
     def total_tokens(self) -> int:
         return int(sum(self.seq_lens))
 
-    def keep_len(self) -> np.ndarray:
-        out = []
-        for S in self.seq_lens:
-            if self.keep_fixed > 0:
-                k = self.keep_fixed
-            else:
-                k = (self.keep_num * S + self.keep_den // 2) // self.keep_den
-            k = max(k, self.keep_floor, min(self.w, S))
-            out.append(min(k, S))
-        return np.asarray(out, dtype=np.int32)
+    def schedule_args(self):
+        """(num, den, floor) of this workload's retention rule, in the form the schedule functions of the
+        library and of the oracle take; a fixed count is the ratio 0 with that count as the floor.  The
+        rule itself is not evaluated here: each side computes its keep counts with its own schedule."""
+        if self.keep_fixed > 0:
+            return 0, 1, int(self.keep_fixed)
+        return int(self.keep_num), int(self.keep_den), int(self.keep_floor)
 
     def seq_offsets(self) -> np.ndarray:
         return np.concatenate([[0], np.cumsum(self.seq_lens)]).astype(np.int32)
@@ -151,7 +148,8 @@ def make_inputs(wl: Workload, layer: int = 0, want_hidden: bool = True, threads:
 
     Returns a dict of numpy arrays: q [T,Hq,d], k, v [T,Hkv,d] (uint16 bf16 bit
     patterns), hidden [T,D] (if the workload has one), seq_offsets int32 [B+1],
-    keep_len int32 [B], heavy (list per sequence of planted local positions).
+    heavy (list per sequence of planted local positions).  The keep counts are not
+    part of the inputs: they come from the schedule of whoever consumes them.
     Every sequence has its own counter-seeded generator, so any subset of
     sequences can be regenerated alone and the result does not depend on the
     number of worker threads.
@@ -168,7 +166,6 @@ def make_inputs(wl: Workload, layer: int = 0, want_hidden: bool = True, threads:
         "k": np.concatenate([p["k"] for p in parts], axis=0),
         "v": np.concatenate([p["v"] for p in parts], axis=0),
         "seq_offsets": wl.seq_offsets(),
-        "keep_len": wl.keep_len(),
         "heavy": [p["heavy"] for p in parts],
     }
     if want_hidden and wl.hidden_dim > 0:

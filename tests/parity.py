@@ -1,11 +1,34 @@
 """Shared comparison helpers of the GPU parity tests (no GPU code, no oracle arithmetic)."""
 import numpy as np
 
+from oracle import pyr_oracle as orc
+
 OUT_MAX_ABS = 2e-2        # attention output, bf16 in / fp32 accumulate
 OUT_MEAN_ABS = 2e-3
 SCORE_RTOL = 1e-3         # token scores
 SCORE_ATOL = 1e-10        # only guards scores that are exactly or almost zero
 BAND = 1e-3               # relative half-width of the tie band at the k-th score
+
+
+def keep_lens(wl, lib=None):
+    """Keep count of every sequence of a workload.  The input generator only names the rule
+    (ratio, floor); the oracle side evaluates it with the oracle's schedule and, when `lib` (the
+    C-ABI binding) is given, the library side with pyr_schedule_next: both must agree before
+    anything is launched with them."""
+    num, den, floor = wl.schedule_args()
+    ref = np.asarray([orc.schedule_next(S, wl.w, num, den, floor) for S in wl.seq_lens], dtype=np.int32)
+    if lib is not None:
+        got = np.asarray([lib.schedule_next(S, wl.w, num, den, floor) for S in wl.seq_lens], dtype=np.int32)
+        assert got.tolist() == ref.tolist(), "library and oracle schedules disagree"
+    return ref
+
+
+def inputs(wl, lib=None, **kw):
+    """synth.make_inputs plus the keep counts (see keep_lens)."""
+    from paper_2405_12532_amd import synth
+    x = synth.make_inputs(wl, **kw)
+    x["keep_len"] = keep_lens(wl, lib)
+    return x
 
 
 def check_index_sets(kept_gpu, ref, seq_offsets, keep_len, w):

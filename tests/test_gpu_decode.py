@@ -25,7 +25,7 @@ def window_queries(q_bits, seq_offsets, w):
 
 
 def run_and_check(lib, wl, row_weights=None, with_pos=False, scale=0.0):
-    x = synth.make_inputs(wl, want_hidden=False)
+    x = parity.inputs(wl, lib, want_hidden=False)
     off, keep = x["seq_offsets"], x["keep_len"]
     q_win = window_queries(x["q"], off, wl.w)
     pos = np.random.default_rng(3).integers(0, 1 << 20, x["k"].shape[0]).astype(np.int32) if with_pos else None

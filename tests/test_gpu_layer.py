@@ -12,7 +12,7 @@ F64 = synth.bf16_bits_to_f64
 
 
 def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=None, row_weights=None, pos=None):
-    x = synth.make_inputs(wl, layer=layer) if x is None else x
+    x = parity.inputs(wl, lib, layer=layer) if x is None else x
     hid = x.get("hidden") if hidden else None
     res = lib.prefill_layer_from_numpy(x, wl.w, hidden=hid, softmax_scale=scale, row_weights=row_weights, pos=pos)
     ref = orc.prefill_layer(F64(x["q"]), F64(x["k"]), F64(x["v"]), x["seq_offsets"], wl.w, x["keep_len"],
@@ -80,7 +80,7 @@ def test_degenerate_keep_lengths(lib):
     """keep everything (identity), keep only the window ("local"), sequences shorter than the window."""
     base = synth.shrunk(synth.workload("cfg2"), (300, 300, 10, 64), n_q_heads=4, n_kv_heads=2, head_dim=64, w=64,
                         hidden_dim=64)
-    x = synth.make_inputs(base)
+    x = parity.inputs(base, lib)
     x["keep_len"] = np.asarray([300, 64, 10, 64], dtype=np.int32)
     res, ref, _ = run_and_check(lib, base, x=x)
     assert res["kept_idx"][:300].tolist() == list(range(300))
@@ -92,7 +92,7 @@ def test_zero_keys_uniform_attention_full_tie(lib):
     tail (closed form), and context scores before the window are all equal, so the tie rule
     alone decides the selection: the lowest positions win."""
     wl = synth.shrunk(synth.workload("cfg1"), (400,), n_q_heads=4, n_kv_heads=4, head_dim=64, w=16, keep_fixed=100)
-    x = synth.make_inputs(wl)
+    x = parity.inputs(wl, lib)
     x["k"][:] = 0
     res, ref, _ = run_and_check(lib, wl, x=x)
     S, L = 400, 16
@@ -103,7 +103,7 @@ def test_zero_keys_uniform_attention_full_tie(lib):
 
 def test_layer_is_bit_reproducible(lib):
     wl = synth.shrunk(synth.workload("cfg2"), (900, 333), n_q_heads=8, n_kv_heads=8, head_dim=128, w=64)
-    x = synth.make_inputs(wl)
+    x = parity.inputs(wl, lib)
     a = lib.prefill_layer_from_numpy(x, wl.w)
     b = lib.prefill_layer_from_numpy(x, wl.w)
     for name in ("out", "scores", "kept_idx", "lse"):

@@ -127,7 +127,7 @@ def sample_rows(S, w, n_random, rng, full=False):
 
 def run_workload(lib, wl, seqs, n_random_rows, full_seq=None, layer=0, seed=0):
     t0 = time.time()
-    x = synth.make_inputs(wl, layer=layer)
+    x = parity.inputs(wl, lib, layer=layer)
     hid = lib.to_device_bf16(x["hidden"]) if "hidden" in x else None
     dl = DeviceLayer(lib, x, wl, hid)
     t1 = time.time()
@@ -190,7 +190,7 @@ class PyramidChain:
         B, S = base.n_seqs, self.lengths[-1]
         t0 = time.time()
         wl = synth.shrunk(base, (S,) * B)
-        x = synth.make_inputs(wl, layer=layer, want_hidden=False)
+        x = parity.inputs(wl, lib, layer=layer, want_hidden=False)
         assert int(x["keep_len"][0]) == lib.schedule_next(S, wl.w, 93, 100, 192)
         dl = DeviceLayer(lib, x, wl, self.hid_dev)
         dl.run()

@@ -52,6 +52,17 @@ def test_schedule_matches_oracle_and_golden():
         assert e.value.status == -2
 
 
+def test_workload_keep_counts_agree_between_library_and_oracle():
+    """The input generator holds no schedule arithmetic: each side derives its own counts, and they agree."""
+    from paper_2405_12532_amd import synth
+    from tests import parity
+    for name in ["cfg1", "cfg2", "64x2k", "cfg4", "cfg5"]:
+        wl = synth.workload(name)
+        keep = parity.keep_lens(wl, binding)
+        assert len(keep) == wl.n_seqs and all(min(wl.w, S) <= k <= S for k, S in zip(keep, wl.seq_lens))
+    assert not hasattr(synth.Workload, "keep_len")
+
+
 def test_workspace_bytes():
     s = binding.make_shape(3, 1000, 512, 8, 2, 128)
     n = binding.workspace_bytes(s, 16)

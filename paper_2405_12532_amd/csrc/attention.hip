@@ -774,39 +774,25 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     __builtin_amdgcn_s_waitcnt(0x0f70);           // no load may still be writing LDS when the workgroup ends
 }
 
-int device_slots() {
-    static int slots = 0;            // workgroups the device holds at one per compute unit
-    if (slots == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-        slots = cus;
-    }
-    return slots;
-}
-
 template <int D>
 int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
                        const pyr_shape& s, int32_t uniform_len, int64_t total_items, float c,
                        void* out, float* lse, int32_t* item_map, hipStream_t stream) {
     auto kern = attention_kernel<D>;
-    static bool attr_done = false;   // benign race: the attribute call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)Tile<D>::kLdsBytes) != hipSuccess)
-            return PYR_ERR_LAUNCH;
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set{0};
+    if (ensure_dynamic_lds((const void*)kern, (int)Tile<D>::kLdsBytes, &lds_set) != PYR_OK) return PYR_ERR_LAUNCH;
     if (total_items == 0) return PYR_OK;
+    DeviceInfo dev;
+    if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
     if (uniform_len == 0) {
         hipLaunchKernelGGL(item_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs, item_map);
         if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
     }
-    const int xcds = (s.n_kv_heads % 8 == 0) ? 8 : 1;
+    // Workgroup ids go round robin over the XCDs; the items are split by KV head so that one XCD's L2 serves
+    // one head's K/V rows.  That needs the KV heads to divide evenly; otherwise one list for the whole device.
+    const int xcds = (s.n_kv_heads % dev.xccs == 0 && dev.compute_units % dev.xccs == 0) ? dev.xccs : 1;
     const int32_t items_per_xcd = (int32_t)((long long)total_items * s.n_q_heads / xcds);
-    long long per_xcd_slots = device_slots() / xcds;
-    if (per_xcd_slots < 1) per_xcd_slots = 1;
+    long long per_xcd_slots = dev.compute_units / xcds;          // one persistent workgroup per compute unit
     if (per_xcd_slots > items_per_xcd) per_xcd_slots = items_per_xcd;
     const unsigned grid = (unsigned)(per_xcd_slots * xcds);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), Tile<D>::kLdsBytes, stream,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/pyr.h"
 
 namespace pyr {
@@ -47,6 +49,14 @@ int launch_window_score(const void* q_win, const void* k, const int32_t* seq_off
 
 int launch_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept, int32_t* pos_out,
                             hipStream_t stream);
+
+// Compute units and XCDs of the current device (cached per device); PYR_ERR_LAUNCH if the runtime
+// cannot tell - the launchers do not guess.
+struct DeviceInfo { int device, compute_units, xccs; };
+int device_info(DeviceInfo* out);
+
+// Raise a kernel's dynamic LDS limit to `bytes`, once per device (done_mask: one bit per device id).
+int ensure_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>* done_mask);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? PYR_OK : PYR_ERR_LAUNCH; }
 

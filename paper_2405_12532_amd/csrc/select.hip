@@ -195,11 +195,9 @@ int launch_select(const float* scores, const int32_t* seq_offsets_dev, const int
     if (n_seqs == 0) return PYR_OK;
     int staged = max_seqlen < kLdsKeys ? max_seqlen : kLdsKeys;
     size_t lds_bytes = (size_t)staged * sizeof(uint32_t);
-    if (lds_bytes > 48 * 1024) {
-        if (hipFuncSetAttribute((const void*)select_topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds_bytes) != hipSuccess)
-            return PYR_ERR_LAUNCH;
-    }
+    static std::atomic<uint64_t> lds_set{0};          // the limit is raised once per device, to the most the kernel ever asks for
+    if (ensure_dynamic_lds((const void*)select_topk_kernel, kLdsKeys * (int)sizeof(uint32_t), &lds_set) != PYR_OK)
+        return PYR_ERR_LAUNCH;
     hipLaunchKernelGGL(select_topk_kernel, dim3(n_seqs), dim3(kThreads), lds_bytes, stream,
                        scores, seq_offsets_dev, keep_len_dev, n_seqs, w, (int32_t)staged, kept_idx, out_offsets_dev);
     return check_launch();

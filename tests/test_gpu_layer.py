@@ -11,7 +11,8 @@ torch = pytest.importorskip("torch")
 F64 = synth.bf16_bits_to_f64
 
 
-def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=None, row_weights=None, pos=None):
+def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=None, row_weights=None, pos=None,
+                  check_out=parity.check_out):
     x = parity.inputs(wl, lib, layer=layer) if x is None else x
     hid = x.get("hidden") if hidden else None
     res = lib.prefill_layer_from_numpy(x, wl.w, hidden=hid, softmax_scale=scale, row_weights=row_weights, pos=pos)
@@ -19,7 +20,7 @@ def run_and_check(lib, wl, layer=0, out_rows=None, hidden=True, scale=0.0, x=Non
                             scale=scale if scale > 0 else None, out_rows=out_rows, row_weights=row_weights, pos=pos)
     if pos is not None:
         assert np.array_equal(res["pos_out"], pos[res["kept_idx"]]), "position ids must follow the kept rows exactly"
-    mx, mean = parity.check_out(res["out"], ref, x["seq_offsets"], F64)
+    mx, mean = check_out(res["out"], ref, x["seq_offsets"], F64)
     rel = parity.check_scores(res["scores"], ref)
     same, swapped = parity.check_index_sets(res["kept_idx"], ref, x["seq_offsets"], x["keep_len"], wl.w)
     assert res["out_offsets"].tolist() == ref["out_offsets"].tolist()

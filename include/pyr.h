@@ -46,8 +46,12 @@ typedef enum pyr_status {
     PYR_ERR_KEEP_LEN = -4,    /* keep_len[b] outside [min(w, S_b), S_b]                   */
     PYR_ERR_OFFSETS = -5,     /* seq_offsets not 0-based, not monotone, or != T at end    */
     PYR_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned (256 B) or too small          */
-    PYR_ERR_LAUNCH = -7       /* the HIP runtime refused a launch (see hipGetLastError)   */
+    PYR_ERR_LAUNCH = -7,      /* the HIP runtime refused a launch (see hipGetLastError)   */
+    PYR_ERR_TOO_LARGE = -8    /* needs more than PYR_STATIC_SCRATCH_BYTES of workspace     */
 } pyr_status;
+
+/* Size of the library's own workspace buffer (see pyr_prefill_layer_static). */
+#define PYR_STATIC_SCRATCH_BYTES ((size_t)40 << 20)
 
 typedef struct pyr_shape {
     int32_t n_seqs;       /* B                                   */
@@ -206,6 +210,26 @@ PYR_API int pyr_prefill_layer(const void* q, const void* k, const void* v,
                       void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
                       void* k_out, void* v_out,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * pyr_prefill_layer for callers that cannot hand over a workspace they allocated: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * `workspace`; the workspace is a buffer inside the library's device image instead
+ * (PYR_STATIC_SCRATCH_BYTES = 40 MiB per GPU the library runs on, held until the process ends;
+ * enough for every shape with pyr_workspace_bytes() <= 40 MiB, i.e. T*Hq <= about 10.4 M rows x heads:
+ * 64 x 2048 tokens x 32 heads uses 16 MiB, 4 x 32768 x 64 heads 32 MiB).  The call allocates
+ * and frees nothing; the first call on a device looks the buffer's address up.
+ *   - a larger step returns PYR_ERR_TOO_LARGE and launches nothing;
+ *   - all calls on one GPU share the buffer: calls that overlap in time on one GPU (different
+ *     streams or threads) race; serialise them or use pyr_prefill_layer with separate workspaces;
+ *   - results are identical to pyr_prefill_layer's.
+ */
+PYR_API int pyr_prefill_layer_static(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, void* stream);
 
 /*
  * The same with the two optional extras: averaging weights for step 2 (see

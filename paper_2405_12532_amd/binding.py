@@ -43,6 +43,8 @@ _SIGNATURES = {
     "pyr_gather_positions": (ctypes.c_int, [_VP, _VP, _I64, _VP, _VP]),
     "pyr_prefill_layer_ex": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                             _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
+    "pyr_prefill_layer_static": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
+                                                _VP, _VP, _VP, _VP, _VP, _VP, _VP]),
     "pyr_decode_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(PyrShape), _I32, ctypes.POINTER(_SZ)]),
     "pyr_decode_update": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                          _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
@@ -178,6 +180,15 @@ def prefill_layer(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_
                                     _ptr(keep_len_host), _ptr(out), _ptr(scores), _ptr(kept_idx),
                                     _ptr(out_offsets_dev), _ptr(k_out), _ptr(v_out), _ptr(workspace),
                                     int(workspace_bytes_), _stream(stream)), "pyr_prefill_layer")
+
+
+def prefill_layer_static(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev,
+                         keep_len_host, out, scores, kept_idx, out_offsets_dev, k_out, v_out, stream=None):
+    _check(load().pyr_prefill_layer_static(_ptr(q), _ptr(k), _ptr(v), _ptr(seq_offsets_dev), _ptr(seq_offsets_host),
+                                           ctypes.byref(shape), int(w), float(softmax_scale), _ptr(keep_len_dev),
+                                           _ptr(keep_len_host), _ptr(out), _ptr(scores), _ptr(kept_idx),
+                                           _ptr(out_offsets_dev), _ptr(k_out), _ptr(v_out), _stream(stream)),
+           "pyr_prefill_layer_static")
 
 
 def decode_workspace_bytes(shape: PyrShape, w: int) -> int:

@@ -4,6 +4,12 @@
 
 #include "pyr_internal.h"
 
+// Device memory of pyr_prefill_layer_static: the workspace of one layer step, held by every GPU the
+// library runs on until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returns (static_scratch()).
+constexpr size_t kStaticScratchBytes = PYR_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -70,6 +76,21 @@ float scale_log2(float softmax_scale, int head_dim) {
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// Address of `scratch` on the current device, looked up once per device (every GPU has its own copy of
+// the array at its own address); nullptr if the runtime cannot resolve it.
+void* static_scratch() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> ptrs[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = ptrs[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+        ptrs[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -84,6 +105,7 @@ const char* pyr_strerror(int status) {
         case PYR_ERR_OFFSETS: return "seq_offsets not 0-based, not monotone or not ending at total_tokens";
         case PYR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case PYR_ERR_LAUNCH: return "HIP launch failed";
+        case PYR_ERR_TOO_LARGE: return "the step needs more workspace than the library's static buffer holds";
         default: return "unknown pyr status";
     }
 }
@@ -283,6 +305,25 @@ int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
     }
     if (pos != nullptr && total_kept > 0) rc = pyr::launch_gather_positions(pos, kept_idx, total_kept, pos_out, st);
     return rc;
+}
+
+int pyr_prefill_layer_static(const void* q, const void* k, const void* v,
+                             const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                             const pyr_shape* shape, int32_t w, float softmax_scale,
+                             const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                             void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                             void* k_out, void* v_out, void* stream) {
+    size_t need = 0;
+    const int rc = pyr_workspace_bytes(shape, w, &need);
+    if (rc != PYR_OK) return rc;
+    if (need > kStaticScratchBytes) return PYR_ERR_TOO_LARGE;
+    void* ws = static_scratch();
+    if (ws == nullptr) return PYR_ERR_LAUNCH;
+    // Nothing in the workspace has to start at zero: the row statistics and the tile map are written in full
+    // by the step's first kernels before anything reads them, so the last call's contents do not matter.
+    return pyr_prefill_layer_ex(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev,
+                                keep_len_host, nullptr, nullptr, out, scores, kept_idx, out_offsets_dev, k_out, v_out,
+                                nullptr, ws, kStaticScratchBytes, stream);
 }
 
 int pyr_decode_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out) {

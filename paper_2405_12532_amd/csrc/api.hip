@@ -18,7 +18,6 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct BatchInfo {
     int32_t uniform_len;    // common length if all sequences have one (> 0), else 0
     int32_t max_len;
-    int64_t q_tiles;        // attention work items per head: sum over sequences of ceil(ceil(S_b / kAttnBlockRows) / 2)
 };
 
 int check_shape(const pyr_shape* s) {
@@ -38,20 +37,17 @@ int check_offsets(const int32_t* off, int32_t n_seqs, int32_t total, int32_t max
     if (off[0] != 0) return PYR_ERR_OFFSETS;
     int32_t max_len = 0, first = n_seqs > 0 ? off[1] - off[0] : 0;
     bool uniform = n_seqs > 0;
-    int64_t tiles = 0;
     for (int32_t b = 0; b < n_seqs; ++b) {
         if (off[b + 1] < off[b]) return PYR_ERR_OFFSETS;
         const int32_t len = off[b + 1] - off[b];
         if (len > max_len) max_len = len;
         if (len != first) uniform = false;
-        tiles += ((len + pyr::kAttnBlockRows - 1) / pyr::kAttnBlockRows + 1) / 2;
     }
     if (off[n_seqs] != total) return PYR_ERR_OFFSETS;
     if (max_len_claimed >= 0 && max_len > max_len_claimed) return PYR_ERR_SHAPE;
     if (info != nullptr) {
         info->uniform_len = (uniform && first > 0) ? first : 0;
         info->max_len = max_len;
-        info->q_tiles = tiles;
     }
     return PYR_OK;
 }
@@ -164,9 +160,8 @@ int pyr_attention(const void* q, const void* k, const void* v,
     BatchInfo info;
     rc = check_offsets(seq_offsets_host, shape->n_seqs, shape->total_tokens, shape->max_seqlen, &info);
     if (rc != PYR_OK) return rc;
-    if (info.uniform_len == 0 && info.q_tiles > 0 && tile_map == nullptr) return PYR_ERR_WORKSPACE;
-    if (info.q_tiles * shape->n_q_heads >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
-    return pyr::launch_attention(q, k, v, seq_offsets_dev, *shape, info.uniform_len, info.q_tiles,
+    if (info.uniform_len == 0 && shape->total_tokens > 0 && tile_map == nullptr) return PYR_ERR_WORKSPACE;
+    return pyr::launch_attention(q, k, v, seq_offsets_dev, seq_offsets_host, *shape, info.uniform_len,
                                  scale_log2(softmax_scale, shape->head_dim), out, lse, tile_map,
                                  (hipStream_t)stream);
 }
@@ -281,7 +276,6 @@ int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
     rc = pyr_workspace_bytes(shape, w, &need);
     if (rc != PYR_OK) return rc;
     if (workspace == nullptr || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return PYR_ERR_WORKSPACE;
-    if (info.q_tiles * shape->n_q_heads >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
 
     float* lse = (float*)workspace;
     int32_t* tile_map =
@@ -291,7 +285,7 @@ int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
     pyr_shape s = *shape;
     s.max_seqlen = info.max_len;
 
-    rc = pyr::launch_attention(q, k, v, seq_offsets_dev, s, info.uniform_len, info.q_tiles, c, out, lse, tile_map, st);
+    rc = pyr::launch_attention(q, k, v, seq_offsets_dev, seq_offsets_host, s, info.uniform_len, c, out, lse, tile_map, st);
     if (rc != PYR_OK) return rc;
     rc = pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, c, row_weights_dev, scores, st);
     if (rc != PYR_OK) return rc;

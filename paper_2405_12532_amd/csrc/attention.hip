@@ -58,10 +58,7 @@ namespace pyr {
 namespace {
 
 constexpr int kBN = 64;                    // key positions per LDS tile
-constexpr int kNW = 8;                     // wavefronts per workgroup
-constexpr int kBM = kNW * 32;              // query positions per segment
 constexpr int kRing = 4;                   // LDS tiles per ring (one ring for K, one for V)
-static_assert(kBM == kAttnBlockRows, "the host counts items with this segment height");
 
 // LDS image of one K or V tile: 64 rows of D bf16, NO padding (the direct global->LDS loads
 // fill 1 KiB of consecutive LDS per wavefront instruction).  Bank conflicts are avoided by an
@@ -70,7 +67,7 @@ static_assert(kBM == kAttnBlockRows, "the host counts items with this segment he
 //   V: chunk ^ ((row & 3) << 2)  -> the 4 rows x 64 B a transposing read touches tile the banks
 // (for D = 64 two rows share a 256-byte bank line: row is replaced by row / 2 and the masks
 // shrink to 7 and 1).
-template <int D>
+template <int D, int kNW>
 struct Tile {
     static constexpr int kChunks = D / 8;                       // 16-byte chunks per row
     static constexpr int kRowBytes = D * 2;
@@ -124,19 +121,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {      // v_cvt_
     return __builtin_bit_cast(uint32_t, v);
 }
 
-__device__ __forceinline__ int items_of(int seq_len) {       // paired query tiles of one (sequence, head)
-    return ((seq_len + kBM - 1) / kBM + 1) / 2;
+__host__ __device__ __forceinline__ int items_of(int seq_len, int block_rows) {       // paired query tiles of one (sequence, head)
+    return ((seq_len + block_rows - 1) / block_rows + 1) / 2;
 }
 
 // prefix sums of the number of items per (sequence, head) (ragged batches only)
 __global__ __launch_bounds__(1024) void item_map_kernel(const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
-                                                        int32_t* __restrict__ item_map) {
+                                                        int32_t block_rows, int32_t* __restrict__ item_map) {
     __shared__ int part[1024];
     const int tid = threadIdx.x;
     const int chunk = (n_seqs + 1023) / 1024;
     const int lo = min(tid * chunk, n_seqs), hi = min(lo + chunk, n_seqs);
     int sum = 0;
-    for (int b = lo; b < hi; ++b) sum += items_of(seq_offsets[b + 1] - seq_offsets[b]);
+    for (int b = lo; b < hi; ++b) sum += items_of(seq_offsets[b + 1] - seq_offsets[b], block_rows);
     part[tid] = sum;
     __syncthreads();
     for (int d = 1; d < 1024; d <<= 1) {
@@ -148,7 +145,7 @@ __global__ __launch_bounds__(1024) void item_map_kernel(const int32_t* __restric
     int run = part[tid] - sum;
     for (int b = lo; b < hi; ++b) {
         item_map[b] = run;
-        run += items_of(seq_offsets[b + 1] - seq_offsets[b]);
+        run += items_of(seq_offsets[b + 1] - seq_offsets[b], block_rows);
     }
     if (tid == 1023) item_map[n_seqs] = part[1023];
 }
@@ -164,20 +161,21 @@ struct Segment {                // all fields wave-uniform
 // A position in the workgroup's list of segments (and, for the load cursors, in the stream
 // of key tiles).  All fields wave-uniform.
 struct Walker {
-    int item;                   // index inside this XCD's item list
+    int j;                      // index inside this workgroup's list of items
     int phase;                  // 0: the late (long) tile of the pair, 1: the early one
     int pair, nq;               // decoded item: pair index, query tiles of the sequence
     int t;                      // key tile inside the segment (load cursors only)
     Segment seg;
 };
 
-template <int D>
+template <int D, int kNW>
 __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ item_map,
     int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds,
-    int32_t items_per_xcd, float c, uint16_t* __restrict__ out, float* __restrict__ lse) {
-    using T = Tile<D>;
+    int32_t items_per_xcd, int32_t first_wave_slots, float c, uint16_t* __restrict__ out, float* __restrict__ lse) {
+    using T = Tile<D, kNW>;
+    constexpr int kBM = kNW * 32;                 // query positions per segment
     constexpr int NS = D / 16;                    // MFMAs per group = k-steps of QK^T = V fragments of a half
     constexpr int kDTiles = D / 32;               // 32-row tiles of O^T
     constexpr int EPS = 8 / NS;                   // logits of a chunk handled per slice (1 or 2)
@@ -192,7 +190,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rb = wave < 4 ? wave : 11 - wave;   // 32-row block of this wavefront (SIMD s: blocks s and 7-s)
+    // 32-row block of this wavefront.  Eight wavefronts: SIMD s owns blocks s and 7-s.  Four: one wavefront per
+    // SIMD, and the second workgroup of a compute unit (slot >= first_wave_slots) deals the blocks the other
+    // way round, so that the two wavefronts sharing a SIMD again own blocks s and 3-s.
+    const int rb = kNW == 8 ? (wave < 4 ? wave : 11 - wave)
+                            : ((int)(blockIdx.x / xcds) >= first_wave_slots ? kNW - 1 - wave : wave);
     const int li = lane & 31;                     // row (A operand) / column (B, C) inside a 32-wide tile
     const int gl = lane >> 5;                     // which half of the k-slots / accumulator rows
     const int group = n_q_heads / n_kv_heads;
@@ -205,35 +207,64 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     const int slot_stride = gridDim.x / xcds;
     const int per_item = (n_kv_heads / xcds) * group;    // (the host checked that the item count fits 31 bits)
 
-    // decode w.item / w.phase into w.seg; false when the list is exhausted
-    auto decode = [&](Walker& w) __attribute__((always_inline)) -> bool {
-        if (w.item >= items_per_xcd) return false;
-        Segment& sg = w.seg;
-        if (w.phase == 0) {
+    // This workgroup takes the items first, first + stride, ... of its XCD's list.  Turning an item number
+    // into (sequence, heads, tile pair) costs integer divisions (or a search through the ragged batch's
+    // prefix sums), far too slow for the scalar unit at a change of segment; so the lanes do it, 64 items at
+    // a time: lane l of every wavefront holds item tbl_base + l of the workgroup's list, decoded, in four
+    // registers, and a walker fetches an entry with four v_readlane.
+    const int first_item = blockIdx.x / xcds;
+    const int n_mine = (items_per_xcd - first_item + slot_stride - 1) / slot_stride;
+    int tbl_base = 0;
+    int t_row0 = 0, t_len = 0, t_heads = 0, t_pair = 0;       // per lane: first row, length, h | kvh << 16, pair | tiles << 16
+    auto fill_table = [&](int base) __attribute__((always_inline)) {
+        tbl_base = base;
+        const int jj = base + lane;
+        if (jj < n_mine) {
+            const int item = first_item + jj * slot_stride;
             int before, b, n_items;
             if (uniform_len > 0) {
-                n_items = items_of(uniform_len);
-                b = w.item / (per_item * n_items);
+                n_items = items_of(uniform_len, kBM);
+                b = item / (per_item * n_items);
                 before = b * n_items;
             } else {
                 int lo = 0, hi = n_seqs;
                 while (hi - lo > 1) {
                     const int mid = (lo + hi) >> 1;
-                    if (per_item * item_map[mid] <= w.item) lo = mid; else hi = mid;
+                    if (per_item * item_map[mid] <= item) lo = mid; else hi = mid;
                 }
                 b = lo;
                 before = item_map[lo];
                 n_items = item_map[lo + 1] - item_map[lo];
             }
-            const int rem = w.item - per_item * before;
+            const int rem = item - per_item * before;
             const int kv_local = rem / (n_items * group);
             const int rem2 = rem % (n_items * group);
-            w.pair = rem2 / group;
-            sg.kvh = kv_local * xcds + xcd;
-            sg.h = sg.kvh * group + rem2 % group;
-            sg.row0 = uniform_len > 0 ? b * uniform_len : seq_offsets[b];
-            sg.S = uniform_len > 0 ? uniform_len : seq_offsets[b + 1] - sg.row0;
-            w.nq = (sg.S + kBM - 1) / kBM;
+            const int kvh = kv_local * xcds + xcd;
+            t_row0 = uniform_len > 0 ? b * uniform_len : seq_offsets[b];
+            t_len = uniform_len > 0 ? uniform_len : seq_offsets[b + 1] - t_row0;
+            t_heads = (kvh * group + rem2 % group) | (kvh << 16);
+            t_pair = (rem2 / group) | (((t_len + kBM - 1) / kBM) << 16);
+        }
+        // The entries may come out of global loads (ragged batches).  Use them once here: the compiler then waits
+        // for those loads now, not at every later fetch - where its wait would also cover the key/value tiles in
+        // flight and the output rows just stored, a full memory latency at every change of segment.
+        asm volatile("" : "+v"(t_row0), "+v"(t_len), "+v"(t_heads), "+v"(t_pair));
+    };
+    // decode w.j / w.phase into w.seg; false when the list is exhausted.  (The table is moved along once per
+    // segment, in the main loop, far enough ahead of every walker: kTableMargin.)
+    constexpr int kTableMargin = 16;              // items a walker may advance during one segment, generously
+    auto decode = [&](Walker& w) __attribute__((always_inline)) -> bool {
+        if (w.j >= n_mine) return false;
+        Segment& sg = w.seg;
+        if (w.phase == 0) {
+            const int rel = w.j - tbl_base;
+            sg.row0 = __builtin_amdgcn_readlane(t_row0, rel);
+            sg.S = __builtin_amdgcn_readlane(t_len, rel);
+            const int hk = __builtin_amdgcn_readlane(t_heads, rel), pn = __builtin_amdgcn_readlane(t_pair, rel);
+            sg.h = hk & 0xffff;
+            sg.kvh = (int)((unsigned)hk >> 16);
+            w.pair = pn & 0xffff;
+            w.nq = (int)((unsigned)pn >> 16);
             sg.q_base = (w.nq - 1 - w.pair) * kBM;
         } else {
             sg.q_base = w.pair * kBM;             // same sequence and head, the early tile
@@ -248,24 +279,13 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
             n.phase = 1;
         } else {
             n.phase = 0;
-            n.item += slot_stride;
+            n.j += 1;
         }
         if (!decode(n)) return false;
         n.t = 0;
         w = n;
         return true;
     };
-    // step a load cursor to the next tile of the stream; past the end it stays on the last tile
-    // (the same tile is then simply loaded again into a free slot, which keeps the number of
-    // loads per step constant)
-    auto next_tile = [&](Walker& w) __attribute__((always_inline)) {
-        if (w.t + 1 < w.seg.n_tiles) {
-            ++w.t;
-        } else {
-            next_segment(w);
-        }
-    };
-
     // ---- per-lane constants of the data movement
     // K/V tiles: instruction i of this wavefront fills LDS rows (wave*kInstrPerWave + i)*kRowsPerInstr ..
     // with lane l writing physical chunk l % kChunks of row l / kChunks; the lane therefore
@@ -381,7 +401,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     };
     // ---- the workgroup's stream of key tiles
     Walker nx;                                    // walks the list of segments one ahead of the arithmetic
-    nx.item = blockIdx.x / xcds;
+    fill_table(0);
+    nx.j = 0;
     nx.phase = 0;
     nx.pair = nx.nq = nx.t = 0;
     if (!decode(nx)) return;
@@ -394,6 +415,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     enter_segment(nx.seg);                        // cs: the segment being computed; nx: the one after it
     bool has_next = next_segment(nx);
     int lslot = 0;                                // ring slot the next K tile is loaded into (V: the slot before it)
+    int q_age = 0;                                // stream positions requested since the next segment's first query half was
 
     // The loads of one stream position: 2 * kInstrPerWave instructions per wavefront, K first.
     auto request_piece = [&](int idx) __attribute__((always_inline)) {
@@ -411,6 +433,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
             kp = pos_of(lc);
         }
         lslot = lslot == kRing - 1 ? 0 : lslot + 1;
+        ++q_age;
         if (k_rag || v_rag || ragged(kp)) {       // rare: the V offsets take over what the K tile had, K gets its own
 #pragma unroll
             for (int i = 0; i < kInstrPerWave; ++i) v_eff[i] = v_goff[i] - (k_goff[i] - k_eff[i]);
@@ -433,7 +456,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     // their steady-state step than the other half, which keeps the two wavefronts of a SIMD half
     // a step apart: while one is between groups (checks, cursor arithmetic, the barrier itself)
     // the other one feeds the matrix pipe.
-    const bool early_sync = wave >= kNW / 2;
+    const bool early_sync = kNW == 8 && wave >= kNW / 2;
 
     // ---- query fragments.  Loads into registers pass the vector memory path at a quarter of the
     // rate of loads that write LDS, and eight of them per wavefront at every change of segment held
@@ -468,9 +491,13 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // in registers: the area may be overwritten
     };
-    // once the current segment's last QK^T has been issued: half 0 into registers, request half 1
+    // Once the current segment's last QK^T has been issued (the fragments are dead): half 0 into registers,
+    // request half 1 into the same area.
     auto q_turn = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // (half 0 may be the youngest load of a very short segment)
+        // Half 0 was requested when the current segment started.  Once a whole stream position has been requested
+        // after it, the wait of the synchronisation just passed has covered it; only in a very short segment it
+        // may still be among the youngest loads.
+        if (q_age == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         q_copy(0);
         q_request(nx.seg, 1);
     };
@@ -479,6 +506,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kInstrPerWave) : "memory");
         q_copy(1);
         if (has_next) q_request(nx.seg, 0);
+        q_age = 0;
     };
     auto sync = [&](bool with_q) __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" :: "n"(2 * kInstrPerWave) : "memory");
@@ -575,11 +603,14 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
                 F[i], __builtin_bit_cast(bf16x8, pp[i / kDTiles]), oacc[i % kDTiles], 0, 0, 0);
             if (e.on) e_slice(*e.se, e.base, i, *e.pe, *e.lsum);
             slice_load(own, next, i);
-            if (loads && (i & 1)) request_piece(i >> 1);
+            if (loads) {
+                if (NS == 2 * kInstrPerWave) request_piece(i);       // one piece per slice
+                else if (i & 1) request_piece(i >> 1);               // one every other slice
+            }
             fence();
         }
     };
-    static_assert(NS / 2 == 2 * kInstrPerWave, "one piece per odd slice covers a stream position");
+    static_assert(NS / 2 == 2 * kInstrPerWave || NS == 2 * kInstrPerWave, "the slices of one group cover a stream position");
     // a chunk of exponentials alone
     auto e_group = [&](const f32x16& se, int ebase, u32x4& pe, float& lsum) __attribute__((always_inline)) {
 #pragma unroll
@@ -769,49 +800,64 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
         }
         if (!has_next) break;
         enter_segment(nx.seg);
+        // keep the item table ahead of both walkers (they are never more than a few items apart)
+        if (max(nx.j, lc.j) + kTableMargin >= tbl_base + 64 && tbl_base + 64 < n_mine) fill_table(min(nx.j, lc.j));
         has_next = next_segment(nx);
     }
     __builtin_amdgcn_s_waitcnt(0x0f70);           // no load may still be writing LDS when the workgroup ends
 }
 
-template <int D>
+template <int D, int kNW>
 int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
-                       const pyr_shape& s, int32_t uniform_len, int64_t total_items, float c,
+                       const int32_t* seq_offsets_host, const pyr_shape& s, int32_t uniform_len, float c,
                        void* out, float* lse, int32_t* item_map, hipStream_t stream) {
-    auto kern = attention_kernel<D>;
+    auto kern = attention_kernel<D, kNW>;
+    using T = Tile<D, kNW>;
+    constexpr int kBM = kNW * 32;
     static std::atomic<uint64_t> lds_set{0};
-    if (ensure_dynamic_lds((const void*)kern, (int)Tile<D>::kLdsBytes, &lds_set) != PYR_OK) return PYR_ERR_LAUNCH;
+    if (ensure_dynamic_lds((const void*)kern, (int)T::kLdsBytes, &lds_set) != PYR_OK) return PYR_ERR_LAUNCH;
+    long long total_items = 0;                       // work items per query head
+    for (int32_t b = 0; b < s.n_seqs; ++b) total_items += items_of(seq_offsets_host[b + 1] - seq_offsets_host[b], kBM);
     if (total_items == 0) return PYR_OK;
+    if (total_items * s.n_q_heads >= (1ll << 31)) return PYR_ERR_UNSUPPORTED;
     DeviceInfo dev;
     if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
+    if (const char* e = getenv("PYR_ATTN_CUS")) dev.compute_units = atoi(e);      // EXPERIMENT
     if (uniform_len == 0) {
-        hipLaunchKernelGGL(item_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs, item_map);
+        hipLaunchKernelGGL(item_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs, (int32_t)kBM, item_map);
         if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
     }
     // Workgroup ids go round robin over the XCDs; the items are split by KV head so that one XCD's L2 serves
     // one head's K/V rows.  That needs the KV heads to divide evenly; otherwise one list for the whole device.
     const int xcds = (s.n_kv_heads % dev.xccs == 0 && dev.compute_units % dev.xccs == 0) ? dev.xccs : 1;
-    const int32_t items_per_xcd = (int32_t)((long long)total_items * s.n_q_heads / xcds);
-    long long per_xcd_slots = dev.compute_units / xcds;          // one persistent workgroup per compute unit
+    const int32_t items_per_xcd = (int32_t)(total_items * s.n_q_heads / xcds);
+    const int wgs_per_cu = (int)(160 * 1024 / T::kLdsBytes) >= 2 ? 2 : 1;    // persistent workgroups, as many as the LDS holds
+    const int32_t first_wave_slots = dev.compute_units / xcds;
+    long long per_xcd_slots = (long long)first_wave_slots * wgs_per_cu;
     if (per_xcd_slots > items_per_xcd) per_xcd_slots = items_per_xcd;
     const unsigned grid = (unsigned)(per_xcd_slots * xcds);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), Tile<D>::kLdsBytes, stream,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), T::kLdsBytes, stream,
                        (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, seq_offsets_dev,
                        (const int32_t*)item_map, s.n_seqs, s.n_q_heads, s.n_kv_heads, uniform_len, xcds,
-                       items_per_xcd, c, (uint16_t*)out, lse);
+                       items_per_xcd, first_wave_slots, c, (uint16_t*)out, lse);
     return check_launch();
 }
 
 }  // namespace
 
 int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
-                     const pyr_shape& shape, int32_t uniform_len, int64_t total_items, float scale_log2,
+                     const int32_t* seq_offsets_host, const pyr_shape& shape, int32_t uniform_len, float scale_log2,
                      void* out, float* lse, int32_t* item_map, hipStream_t stream) {
+    const char* env = getenv("PYR_ATTN_NW");         // EXPERIMENT: wavefronts per workgroup
+    const int nw = env ? atoi(env) : 8;
     if (shape.head_dim == 128)
-        return launch_attention_d<128>(q, k, v, seq_offsets_dev, shape, uniform_len, total_items, scale_log2,
-                                       out, lse, item_map, stream);
-    return launch_attention_d<64>(q, k, v, seq_offsets_dev, shape, uniform_len, total_items, scale_log2,
-                                  out, lse, item_map, stream);
+        return launch_attention_d<128, 8>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                          out, lse, item_map, stream);
+    if (nw == 4)
+        return launch_attention_d<64, 4>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                         out, lse, item_map, stream);
+    return launch_attention_d<64, 8>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                     out, lse, item_map, stream);
 }
 
 }  // namespace pyr

@@ -19,9 +19,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Query positions per attention segment; two segments (tiles j and n-1-j of a sequence) form one work item.
-constexpr int kAttnBlockRows = 256;
-
 // Every launcher returns PYR_OK or PYR_ERR_LAUNCH; arguments are already validated.
 int launch_gather(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
                   const int32_t* kept_idx, int64_t n_kept, hipStream_t stream);
@@ -31,7 +28,7 @@ int launch_select(const float* scores, const int32_t* seq_offsets_dev, const int
                   hipStream_t stream);
 
 int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
-                     const pyr_shape& shape, int32_t uniform_len, int64_t total_items, float scale_log2,
+                     const int32_t* seq_offsets_host, const pyr_shape& shape, int32_t uniform_len, float scale_log2,
                      void* out, float* lse, int32_t* item_map, hipStream_t stream);
 
 // row_weights: device [w] or nullptr (uniform)

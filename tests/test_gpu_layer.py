@@ -72,6 +72,15 @@ def test_small_shapes_complete(lib, lens, Hq, Hkv, d, w):
     run_and_check(lib, wl)
 
 
+def test_many_short_sequences(lib):
+    """2200 sequences of 3..70 tokens: every persistent workgroup walks far more than 64 work items, so the
+    table of decoded items the attention kernel keeps in registers (64 entries) is refilled several times."""
+    rng = np.random.default_rng(11)
+    lens = tuple(int(v) for v in rng.integers(3, 71, size=2200))
+    wl = synth.shrunk(synth.workload("cfg2"), lens, n_q_heads=8, n_kv_heads=8, head_dim=64, w=8, hidden_dim=0)
+    run_and_check(lib, wl, hidden=False)
+
+
 def test_custom_softmax_scale(lib):
     wl = synth.shrunk(synth.workload("cfg2"), (333, 100), n_q_heads=4, n_kv_heads=4, head_dim=64, w=20)
     run_and_check(lib, wl, scale=0.2)

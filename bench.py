@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the PyramidInfer prefill layer step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 64x2k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 64x2k] [--no-extras]
 
 A step is one pass of the whole hot path over one synthetic batch that already sits in
 HBM: causal attention -> recent-window scores -> per-sequence top-k -> gather of K and V
@@ -10,9 +10,13 @@ HBM: causal attention -> recent-window scores -> per-sequence top-k -> gather of
 window 64, 1905 of 2048 tokens kept), i.e. the first layer of the 32-layer pyramid.
 
 The timed region calls the per-step entry points of the C ABI back to back on one stream
-(the same launches pyr_prefill_layer issues) with HIP events between them, so the line
-also carries the average duration of every kernel and the roofline fraction of the
-dominant one.  Prints ONE JSON line.
+with HIP events between them, so the line also carries the duration of every kernel
+(mean, median, minimum) and the roofline fraction of the dominant one.  Beside `value`
+the line reports, as extras that are not part of it: the same step through the merged
+entry point (pyr_prefill_layer_fused), a whole 32-layer pyramid pass at batch 64, the
+small-batch workloads (separate calls against the merged call), the optional parts of the
+step, ceilings measured on this very GPU (MFMA-only loop, device-to-device copy), and the
+float64 oracle timed on the machine's host cores.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -27,14 +31,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
-
-# HBM bytes per launch at the default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script, scaled by what the same counters read for the hidden-row gather (a plain copy of known
-# size); the counter summary is profiles/layer_step_64x2k_pmc.txt.
-MEASURED_TRAFFIC = {
-    ("64x2k", "attention"): 6.55e9,       # 5.34 GB read + 1.21 GB written (algorithmic 4.31 GB)
-    ("64x2k", "gather"): 5.99e9,          # read = written = algorithmic after calibration
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_64x2k.json")   # HBM bytes per launch from rocprofv3 --pmc runs
 
 
 def attention_flops(seq_lens, n_q_heads, head_dim):
@@ -46,8 +43,29 @@ def score_flops(seq_lens, n_q_heads, head_dim, w):
     return float(sum(2 * head_dim * min(w, S) * S * n_q_heads for S in seq_lens))
 
 
-def cpu_baseline(wl, n_seqs_sample):
-    """The float64 oracle, as it stands, on the first n_seqs_sample sequences of the workload."""
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the attention kernel and of the gathers, measured with hardware counters at the
+    commit the file names (see profiles/); None for a workload the file does not cover."""
+    try:
+        t = json.load(open(TRAFFIC_FILE))
+    except OSError:
+        return {}
+    return t.get("bytes_per_launch", {}) if t.get("workload") == workload_name else {}
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(wl, n_seqs_sample, reps=3):
+    """The float64 oracle, as it stands, on the first n_seqs_sample sequences of the workload:
+    one warm-up run, then the median of `reps` runs."""
     import numpy as np
     from oracle import pyr_oracle as orc
     from paper_2405_12532_amd import synth
@@ -58,9 +76,12 @@ def cpu_baseline(wl, n_seqs_sample):
     f = synth.bf16_bits_to_f64
     q, k, v = f(x["q"]), f(x["k"]), f(x["v"])
     hid = x.get("hidden")
-    t0 = time.perf_counter()
-    orc.prefill_layer(q, k, v, x["seq_offsets"], sub.w, keep, hidden=hid)
-    dt = time.perf_counter() - t0
+    times = []
+    for _ in range(reps + 1):
+        t0 = time.perf_counter()
+        orc.prefill_layer(q, k, v, x["seq_offsets"], sub.w, keep, hidden=hid)
+        times.append(time.perf_counter() - t0)
+    dt = float(np.median(times[1:]))
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -68,10 +89,122 @@ def cpu_baseline(wl, n_seqs_sample):
         cores = len(os.sched_getaffinity(0))
     return {
         "value": sub.total_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-        "sample": f"{n_seqs_sample} of {wl.n_seqs} sequences ({sub.total_tokens} tokens, all heads, all rows), "
-                  f"{dt:.2f} s wall, numpy float64",
-        "seconds": dt,
+        "sample": f"{n_seqs_sample} of {wl.n_seqs} sequences ({sub.total_tokens} tokens, all heads, all rows), numpy float64, "
+                  f"1 warm-up + median of {reps} runs ({', '.join('%.2f' % t for t in times[1:])} s; warm-up {times[0]:.2f} s)",
+        "seconds": dt, "cpu": cpu_model(),
     }
+
+
+class Step:
+    """Device buffers of one workload and the two ways to run its layer step."""
+
+    def __init__(self, pyr, synth, wl, x=None):
+        import numpy as np
+        import torch
+        self.pyr, self.wl, self.torch = pyr, wl, torch
+        x = synth.make_inputs(wl) if x is None else x
+        T, Hq, Hkv, d, D = wl.total_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.hidden_dim
+        self.T, self.D = T, D
+        self.q, self.k, self.v = (pyr.to_device_bf16(x[n]) for n in ("q", "k", "v"))
+        self.hidden = pyr.to_device_bf16(x["hidden"]) if D > 0 else None
+        self.off_h = torch.from_numpy(np.ascontiguousarray(x["seq_offsets"], dtype=np.int32))
+        num, den, floor = wl.schedule_args()       # the retention rule of the workload, evaluated by the library's schedule
+        self.keep_h = torch.tensor([pyr.schedule_next(S, wl.w, num, den, floor) for S in wl.seq_lens], dtype=torch.int32)
+        self.off_d, self.keep_d = self.off_h.cuda(), self.keep_h.cuda()
+        self.n_kept = int(self.keep_h.sum())
+        self.shape = pyr.make_shape(wl.n_seqs, T, max(wl.seq_lens), Hq, Hkv, d)
+        self.ws_bytes = pyr.workspace_bytes(self.shape, wl.w)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
+        self.lse = torch.empty((T, Hq), dtype=torch.float32, device="cuda")
+        self.tile_map = torch.empty(wl.n_seqs + 1, dtype=torch.int32, device="cuda")
+        self.out = torch.empty_like(self.q)
+        self.scores = torch.empty(T, dtype=torch.float32, device="cuda")
+        self.kept = torch.empty(self.n_kept, dtype=torch.int32, device="cuda")
+        self.out_off = torch.empty(wl.n_seqs + 1, dtype=torch.int32, device="cuda")
+        self.k_out = torch.empty((self.n_kept, Hkv, d), dtype=torch.bfloat16, device="cuda")
+        self.v_out = torch.empty_like(self.k_out)
+        self.hidden_out = torch.empty((self.n_kept, D), dtype=torch.bfloat16, device="cuda") if D > 0 else None
+        self.kv_row = Hkv * d * 2
+        self.names = ["attention", "score", "select", "gather_kv", "gather_hidden"]
+
+    def separate(self, events=None):
+        """attention, score, select, K+V gather, hidden gather: the per-step entry points, five launches"""
+        pyr, wl = self.pyr, self.wl
+
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        pyr.attention(self.q, self.k, self.v, self.off_d, self.off_h, self.shape, 0.0, self.out, self.lse, self.tile_map)
+        mark(1)
+        pyr.score(self.q, self.k, self.lse, self.off_d, self.off_h, self.shape, wl.w, 0.0, self.scores)
+        mark(2)
+        pyr.select(self.scores, self.off_d, self.off_h, self.keep_d, self.keep_h, wl.n_seqs, wl.w, self.kept, self.out_off)
+        mark(3)
+        pyr.compact2(self.k, self.k_out, self.v, self.v_out, self.kv_row, self.kept, self.n_kept)
+        mark(4)
+        if self.D > 0:
+            pyr.compact(self.hidden, self.D * 2, self.kept, self.n_kept, self.hidden_out)
+        mark(5)
+
+    def fused(self):
+        """the same step through pyr_prefill_layer_fused: three launches"""
+        self.pyr.prefill_layer_fused(self.q, self.k, self.v, self.off_d, self.off_h, self.shape, self.wl.w, 0.0, self.keep_d,
+                                     self.keep_h, None, self.hidden, self.D * 2, None, self.out, self.scores, self.kept,
+                                     self.out_off, self.k_out, self.v_out, self.hidden_out, None, self.ws, self.ws_bytes)
+
+    def time_ms(self, fn, steps, warmup=2):
+        torch = self.torch
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def stats(v):
+    import numpy as np
+    return {"mean": float(np.mean(v)), "median": float(np.median(v)), "min": float(np.min(v))}
+
+
+def pyramid_pass(pyr, synth, st, steps):
+    """All 32 layers of the pyramid at batch 64 on device-resident inputs: layer l runs the merged step on the first
+    64*S_l rows of the layer-0 Q/K/V buffers (same value distribution, surviving length S_l from the library's
+    schedule) and on the hidden rows the layer before it gathered, so hidden rows really travel through 32 gathers."""
+    import torch
+    wl = st.wl
+    B, S0 = wl.n_seqs, wl.seq_lens[0]
+    num, den, floor = wl.schedule_args()
+    lens = [S0]
+    for _ in range(32):
+        lens.append(pyr.schedule_next(lens[-1], wl.w, num, den, floor))
+    layers = []
+    for l in range(32):
+        S, k_next = lens[l], lens[l + 1]
+        off_h = torch.arange(0, B * S + 1, S, dtype=torch.int32)
+        keep_h = torch.full((B,), k_next, dtype=torch.int32)
+        layers.append(dict(S=S, T=B * S, n_kept=B * k_next, off_h=off_h, off_d=off_h.cuda(), keep_h=keep_h, keep_d=keep_h.cuda(),
+                           shape=pyr.make_shape(B, B * S, S, wl.n_q_heads, wl.n_kv_heads, wl.head_dim)))
+    hid = [st.hidden, torch.empty_like(st.hidden)]
+
+    def one_pass():
+        src = 0
+        for L in layers:
+            T, nk = L["T"], L["n_kept"]
+            pyr.prefill_layer_fused(st.q[:T], st.k[:T], st.v[:T], L["off_d"], L["off_h"], L["shape"], wl.w, 0.0, L["keep_d"],
+                                    L["keep_h"], None, hid[src][:T], st.D * 2, None, st.out[:T], st.scores[:T], st.kept[:nk],
+                                    st.out_off, st.k_out[:nk], st.v_out[:nk], hid[1 - src][:nk], None, st.ws, st.ws_bytes)
+            src = 1 - src
+        # (layer 0 reads st.hidden and writes the second buffer, layer 1 reads that and overwrites st.hidden, and so on:
+        #  after the first pass the hidden values are no longer the originals, which does not change what is timed)
+    ms = st.time_ms(one_pass, steps, warmup=1)
+    layer_tokens = B * sum(lens[:32])
+    return {"ms_per_pass": ms, "layer_tokens_per_pass": layer_tokens, "prompt_tokens_per_pass": B * S0,
+            "layer_tokens_per_s": layer_tokens / (ms * 1e-3), "prompt_tokens_per_s": B * S0 / (ms * 1e-3),
+            "lengths": lens, "entry_point": "pyr_prefill_layer_fused, 32 calls"}
 
 
 def main():
@@ -79,8 +212,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="64x2k", help="64x2k (default), cfg1, cfg2, cfg4, cfg5")
-    ap.add_argument("--cpu-seqs", type=int, default=12, help="sequences the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--workload", default="64x2k", help="64x2k (default), cfg1, cfg2, cfg4, cfg5, 1x2k, 1x8k")
+    ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed step (for profiler runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -93,115 +227,33 @@ def main():
         sys.exit("bench.py: no GPU visible")
     pyr.load()
     wl = synth.workload(args.workload)
-    x = synth.make_inputs(wl)
+    st = Step(pyr, synth, wl)
     T, Hq, Hkv, d, D = wl.total_tokens, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.hidden_dim
-
-    q, k, v = (pyr.to_device_bf16(x[n]) for n in ("q", "k", "v"))
-    hidden = pyr.to_device_bf16(x["hidden"]) if D > 0 else None
-    off_h = torch.from_numpy(np.ascontiguousarray(x["seq_offsets"], dtype=np.int32))
-    num, den, floor = wl.schedule_args()       # the retention rule of the workload, evaluated by the library's schedule
-    keep_h = torch.tensor([pyr.schedule_next(S, wl.w, num, den, floor) for S in wl.seq_lens], dtype=torch.int32)
-    off_d, keep_d = off_h.cuda(), keep_h.cuda()
-    n_kept = int(keep_h.sum())
-    shape = pyr.make_shape(wl.n_seqs, T, max(wl.seq_lens), Hq, Hkv, d)
-    ws_bytes = pyr.workspace_bytes(shape, wl.w)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    lse = ws[: T * Hq * 4].view(torch.float32)
-    tile_map = ws[ws_bytes - (((wl.n_seqs + 1) * 4 + 255) // 256 * 256):].view(torch.int32)
-    out = torch.empty_like(q)
-    scores = torch.empty(T, dtype=torch.float32, device="cuda")
-    kept = torch.empty(n_kept, dtype=torch.int32, device="cuda")
-    out_off = torch.empty(wl.n_seqs + 1, dtype=torch.int32, device="cuda")
-    k_out = torch.empty((n_kept, Hkv, d), dtype=torch.bfloat16, device="cuda")
-    v_out = torch.empty_like(k_out)
-    hidden_out = torch.empty((n_kept, D), dtype=torch.bfloat16, device="cuda") if D > 0 else None
-    kv_row = Hkv * d * 2
-
-    names = ["attention", "score", "select", "gather_kv", "gather_hidden"]
-
-    def step(events=None):
-        def mark(i):
-            if events is not None:
-                events[i].record()
-        mark(0)
-        pyr.attention(q, k, v, off_d, off_h, shape, 0.0, out, lse, tile_map)
-        mark(1)
-        pyr.score(q, k, lse, off_d, off_h, shape, wl.w, 0.0, scores)
-        mark(2)
-        pyr.select(scores, off_d, off_h, keep_d, keep_h, wl.n_seqs, wl.w, kept, out_off)
-        mark(3)
-        pyr.compact2(k, k_out, v, v_out, kv_row, kept, n_kept)
-        mark(4)
-        if D > 0:
-            pyr.compact(hidden, D * 2, kept, n_kept, hidden_out)
-        mark(5)
+    n_kept = st.n_kept
 
     for _ in range(args.warmup):
-        step()
+        st.separate()
     torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(evs[i])
+        st.separate(evs[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    kernel_ms = {n: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, n in enumerate(names)}
+    per_kernel = {n: stats([e[i].elapsed_time(e[i + 1]) for e in evs]) for i, n in enumerate(st.names)}
+    kernel_ms = {n: per_kernel[n]["mean"] for n in st.names}
 
-    # the same step through the single entry point, as a cross-check of the decomposed timing
-    def fused_step():
-        pyr.prefill_layer(q, k, v, off_d, off_h, shape, wl.w, 0.0, keep_d, keep_h, out, scores, kept, out_off,
-                          k_out, v_out, ws, ws_bytes)
-        if D > 0:
-            pyr.compact(hidden, D * 2, kept, n_kept, hidden_out)
-    fused_step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        fused_step()
-    torch.cuda.synchronize()
-    fused_ms = (time.perf_counter() - t1) * 1e3 / args.steps
-
-    # the optional extras of the step, timed on their own (not part of `value`): recency-weighted
-    # score pass and the gather of the kept tokens' position ids
-    rw = torch.linspace(0.25, 1.0, wl.w, dtype=torch.float32, device="cuda")
-    pos = torch.arange(T, dtype=torch.int32, device="cuda")
-    pos_out = torch.empty(n_kept, dtype=torch.int32, device="cuda")
-    ex = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for i in range(-1, args.steps):
-        e = ex[max(i, 0)]
-        e[0].record()
-        pyr.score_weighted(q, k, lse, off_d, off_h, shape, wl.w, 0.0, rw, scores)
-        e[1].record()
-        pyr.gather_positions(pos, kept, n_kept, pos_out)
-        e[2].record()
-    torch.cuda.synchronize()
-    extras_ms = {"score_weighted": float(np.mean([e[0].elapsed_time(e[1]) for e in ex])),
-                 "gather_positions": float(np.mean([e[1].elapsed_time(e[2]) for e in ex]))}
-    # generation-phase update of a cache of the same size: the window's queries in their own buffer,
-    # row statistics + fold + score + select + gathers in one call
-    q_win = torch.stack([q[int(off_h[b + 1]) - wl.w:int(off_h[b + 1])] for b in range(wl.n_seqs)]).contiguous() \
-        if min(wl.seq_lens) >= wl.w else None
-    if q_win is not None:
-        dws_bytes = pyr.decode_workspace_bytes(shape, wl.w)
-        dws = torch.empty(dws_bytes, dtype=torch.uint8, device="cuda")
-        de = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
-        for i in range(-1, args.steps):
-            e = de[max(i, 0)]
-            e[0].record()
-            pyr.decode_update(q_win, k, v, off_d, off_h, shape, wl.w, 0.0, keep_d, keep_h, None, pos, scores, kept,
-                              out_off, k_out, v_out, pos_out, dws, dws_bytes)
-            e[1].record()
-        torch.cuda.synchronize()
-        extras_ms["decode_update"] = float(np.mean([e[0].elapsed_time(e[1]) for e in de]))
+    fused_ms = st.time_ms(st.fused, args.steps)
 
     fl = attention_flops(wl.seq_lens, Hq, d)
     att_tflops = fl / (kernel_ms["attention"] * 1e-3) / 1e12
-    compact_bytes = 2.0 * n_kept * (2 * kv_row + D * 2) + 4.0 * n_kept * (2 if D > 0 else 1)
+    compact_bytes = 2.0 * n_kept * (2 * st.kv_row + D * 2) + 4.0 * n_kept * (2 if D > 0 else 1)
     select_bytes = 4.0 * T + 4.0 * n_kept
     sc_ms = kernel_ms["select"] + kernel_ms["gather_kv"] + kernel_ms["gather_hidden"]
     gather_ms = kernel_ms["gather_kv"] + kernel_ms["gather_hidden"]
+    traffic = measured_traffic(wl.name)
 
     line = {
         "metric": "prefill tokens/s through attention + PvC select + compact (one layer step)",
@@ -212,19 +264,93 @@ def main():
         "config": {"workload": f"{wl.name}: {wl.n_seqs} seqs x {max(wl.seq_lens)} tokens (T={T}), Hq={Hq}, Hkv={Hkv}, "
                                f"d={d}, hidden={D}, w={wl.w}, kept={n_kept}",
                    "tokens_per_step": T, "kept_rows": n_kept},
-        "kernel_ms": kernel_ms, "extras_ms": extras_ms, "ms_per_step_single_entry_point": fused_ms,
+        "kernel_ms": kernel_ms, "kernel_ms_median": {n: per_kernel[n]["median"] for n in st.names},
+        "kernel_ms_min": {n: per_kernel[n]["min"] for n in st.names},
+        "ms_per_step_single_entry_point": fused_ms,
         "roofline": {"kernel": "attention", "bound": "mfma", "achieved": att_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": att_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, "attention")),
-                     "flops_per_launch": fl},
+                     "traffic": traffic.get("attention"), "flops_per_launch": fl,
+                     "achieved_at_min_ms": fl / (per_kernel["attention"]["min"] * 1e-3) / 1e12},
         "roofline_select_compact": {
             "kernel": "select + gather_kv + gather_hidden", "bound": "hbm",
             "achieved": (compact_bytes + select_bytes) / (sc_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": (compact_bytes + select_bytes) / (sc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "gather_only_GBs": compact_bytes / (gather_ms * 1e-3) / 1e9,
-            "traffic": MEASURED_TRAFFIC.get((wl.name, "gather")), "bytes_per_step": compact_bytes + select_bytes},
+            "traffic": traffic.get("gather"), "bytes_per_step": compact_bytes + select_bytes},
         "score_tflops": score_flops(wl.seq_lens, Hq, d, wl.w) / (kernel_ms["score"] * 1e-3) / 1e12,
     }
+
+    if not args.no_extras:
+        # ---- ceilings of this very GPU, beside the published peaks
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pyr.diag_mfma_only(200, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        mf = pyr.diag_mfma_only(4000, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_tflops = mf / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2.0 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+        line["measured_ceilings"] = {
+            "mfma_only_bf16_TFLOPs": mfma_tflops, "published_bf16_TFLOPs": PEAK_BF16_TFLOPS,
+            "attention_frac_of_measured_mfma": att_tflops / mfma_tflops,
+            "copy_GBs_read_plus_write": copy_gbs, "published_hbm_GBs": PEAK_HBM_GBS,
+            "gather_frac_of_measured_copy": compact_bytes / (gather_ms * 1e-3) / 1e9 / copy_gbs,
+            "how": "MFMA: pyr_diag_mfma_only, 64000 v_mfma_f32_32x32x16_bf16 per wavefront, 2 wavefronts per SIMD on every "
+                   "compute unit; copy: torch copy_ of 1 GiB device to device, 10 times"}
+
+        # ---- the optional parts of the step, timed on their own
+        rw = torch.linspace(0.25, 1.0, wl.w, dtype=torch.float32, device="cuda")
+        pos = torch.arange(T, dtype=torch.int32, device="cuda")
+        pos_out = torch.empty(n_kept, dtype=torch.int32, device="cuda")
+        extras_ms = {
+            "score_weighted": st.time_ms(lambda: pyr.score_weighted(st.q, st.k, st.lse, st.off_d, st.off_h, st.shape, wl.w, 0.0,
+                                                                    rw, st.scores), args.steps),
+            "gather_positions": st.time_ms(lambda: pyr.gather_positions(pos, st.kept, n_kept, pos_out), args.steps)}
+        if min(wl.seq_lens) >= wl.w:
+            q_win = torch.stack([st.q[int(st.off_h[b + 1]) - wl.w:int(st.off_h[b + 1])] for b in range(wl.n_seqs)]).contiguous()
+            dws_bytes = pyr.decode_workspace_bytes(st.shape, wl.w)
+            dws = torch.empty(dws_bytes, dtype=torch.uint8, device="cuda")
+            extras_ms["decode_update"] = st.time_ms(
+                lambda: pyr.decode_update(q_win, st.k, st.v, st.off_d, st.off_h, st.shape, wl.w, 0.0, st.keep_d, st.keep_h, None,
+                                          pos, st.scores, st.kept, st.out_off, st.k_out, st.v_out, pos_out, dws, dws_bytes),
+                args.steps)
+            del dws, q_win
+        line["extras_ms"] = extras_ms
+
+        # ---- the whole 32-layer pyramid at batch 64 (the default workload is its first layer)
+        if wl.name == "64x2k":
+            line["pyramid_32_layers"] = pyramid_pass(pyr, synth, st, max(2, args.steps // 5))
+
+        # ---- small batch (Appendix A.1: where the selection overhead shows): separate calls against the merged call
+        small = {}
+        for name in ("cfg1", "1x2k", "1x8k"):
+            s2 = Step(pyr, synth, synth.workload(name))
+            evs2 = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(50)]
+            for _ in range(5):
+                s2.separate()
+            torch.cuda.synchronize()
+            for e in evs2:
+                s2.separate(e)
+            torch.cuda.synchronize()
+            km = {n: float(np.median([e[i].elapsed_time(e[i + 1]) for e in evs2])) for i, n in enumerate(s2.names)}
+            small[name] = {"kernel_ms_median_separate_calls": km, "select_over_attention": km["select"] / km["attention"],
+                           "ms_per_step_separate_calls": s2.time_ms(s2.separate, 200, warmup=10),
+                           "ms_per_step_fused_call": s2.time_ms(s2.fused, 200, warmup=10)}
+            del s2
+        line["small_batch"] = small
+
     if args.cpu_seqs > 0:
         line["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_seqs, wl.n_seqs))
     print(json.dumps(line))

@@ -70,8 +70,9 @@ PYR_API int pyr_version(void);
 
 /*
  * Host only.  Bytes of device workspace pyr_prefill_layer needs for this
- * shape and window (row statistics of the softmax for the score pass and the
- * tile map of ragged batches).  Align the buffer to 256 bytes.
+ * shape and window (row statistics of the softmax for the score pass, the
+ * tile map of ragged batches, arrival counters and partial sums of the score
+ * pass).  Align the buffer to 256 bytes.
  */
 PYR_API int pyr_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out);
 
@@ -197,8 +198,9 @@ PYR_API int pyr_gather_positions(const int32_t* pos, const int32_t* kept_idx, in
                          int32_t* pos_out, void* stream);
 
 /*
- * The whole layer step (Algorithm 1, body of the loop, prefill phase):
- * pyr_attention -> pyr_score -> pyr_select -> pyr_compact2 on one stream.
+ * The whole layer step (Algorithm 1, body of the loop, prefill phase): what
+ * pyr_attention -> pyr_score -> pyr_select -> pyr_compact2 compute, on one stream
+ * (see pyr_prefill_layer_fused for how the launches are merged).
  *   scores             dev fp32 [T], written (required: the selection reads it)
  *   k_out, v_out       dev bf16 [sum k_b, Hkv, d]; both NULL skips the gather
  *   workspace          dev, >= pyr_workspace_bytes(), 256-byte aligned
@@ -246,6 +248,29 @@ PYR_API int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The whole layer step in as few launches as it takes (Appendix A.1 and the Limitations section: at small
+ * batch the cost of selecting the PvC eats the gain - there every launch counts): attention; the score pass,
+ * in which the workgroup that completes a sequence's scores selects its PvC at once (sequences of up to 1024
+ * tokens, none empty; otherwise the selection is a launch of its own: with 128 lanes it takes longer than
+ * the launch costs) and, when the batch is too small to
+ * fill the chip with one workgroup per 64 keys, the KV heads are split over several workgroups whose partial
+ * sums the last of them adds in a fixed order; ONE gather for K, V, the hidden rows and the position ids.
+ * pyr_prefill_layer and pyr_prefill_layer_ex are this call without the hidden rows.
+ *   hidden             dev, rows of hidden_row_bytes bytes (a multiple of 16) indexed by packed row; hidden_out
+ *                      dev [sum k_b rows], written; both NULL skips them
+ *   everything else as in pyr_prefill_layer_ex; results are those of the separate calls (scores may differ in
+ *   the last bit when the heads are split: the partial sums are rounded once more).
+ */
+PYR_API int pyr_prefill_layer_fused(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      const float* row_weights_dev, const void* hidden, size_t hidden_row_bytes, const int32_t* pos,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, void* hidden_out, int32_t* pos_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Generation-phase update of one layer's compressed cache (Algorithm 1 with a non-empty
  * cache, KV = cat(PvC_past, KV); Section 4.1, generation phase: the recent window slides
  * over the generated tokens and the PvC is selected again with the prefill phase's
@@ -276,6 +301,16 @@ PYR_API int pyr_decode_update(const void* q_win, const void* k, const void* v,
                       float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
                       void* k_out, void* v_out, int32_t* pos_out,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Diagnostic for the benchmark report, not part of the method: a launch of nothing but bf16 MFMAs
+ * (v_mfma_f32_32x32x16_bf16 back to back, two wavefronts per SIMD, every compute unit), so that the
+ * rate this very GPU sustains can be printed beside the published peak.
+ *   iters              loop trips per wavefront (16 MFMAs each)
+ *   sink_dev           dev, one float (never written in practice)
+ *   flops_out          host, written: floating-point operations of the launch
+ */
+PYR_API int pyr_diag_mfma_only(int32_t iters, float* sink_dev, void* stream, double* flops_out);
 
 #ifdef __cplusplus
 }

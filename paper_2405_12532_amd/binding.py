@@ -43,6 +43,8 @@ _SIGNATURES = {
     "pyr_gather_positions": (ctypes.c_int, [_VP, _VP, _I64, _VP, _VP]),
     "pyr_prefill_layer_ex": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                             _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
+    "pyr_prefill_layer_fused": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
+                                               _VP, _VP, _SZ, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
     "pyr_prefill_layer_static": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                                 _VP, _VP, _VP, _VP, _VP, _VP, _VP]),
     "pyr_decode_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(PyrShape), _I32, ctypes.POINTER(_SZ)]),
@@ -50,6 +52,7 @@ _SIGNATURES = {
                                          _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
     "pyr_prefill_layer": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                          _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
+    "pyr_diag_mfma_only": (ctypes.c_int, [_I32, _VP, _VP, ctypes.POINTER(ctypes.c_double)]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -182,6 +185,17 @@ def prefill_layer(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_
                                     int(workspace_bytes_), _stream(stream)), "pyr_prefill_layer")
 
 
+def prefill_layer_fused(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev, keep_len_host,
+                        row_weights_dev, hidden, hidden_row_bytes, pos, out, scores, kept_idx, out_offsets_dev, k_out, v_out,
+                        hidden_out, pos_out, workspace, workspace_bytes_, stream=None):
+    _check(load().pyr_prefill_layer_fused(_ptr(q), _ptr(k), _ptr(v), _ptr(seq_offsets_dev), _ptr(seq_offsets_host),
+                                          ctypes.byref(shape), int(w), float(softmax_scale), _ptr(keep_len_dev),
+                                          _ptr(keep_len_host), _ptr(row_weights_dev), _ptr(hidden), int(hidden_row_bytes),
+                                          _ptr(pos), _ptr(out), _ptr(scores), _ptr(kept_idx), _ptr(out_offsets_dev),
+                                          _ptr(k_out), _ptr(v_out), _ptr(hidden_out), _ptr(pos_out), _ptr(workspace),
+                                          int(workspace_bytes_), _stream(stream)), "pyr_prefill_layer_fused")
+
+
 def prefill_layer_static(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev,
                          keep_len_host, out, scores, kept_idx, out_offsets_dev, k_out, v_out, stream=None):
     _check(load().pyr_prefill_layer_static(_ptr(q), _ptr(k), _ptr(v), _ptr(seq_offsets_dev), _ptr(seq_offsets_host),
@@ -189,6 +203,13 @@ def prefill_layer_static(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, s
                                            _ptr(keep_len_host), _ptr(out), _ptr(scores), _ptr(kept_idx),
                                            _ptr(out_offsets_dev), _ptr(k_out), _ptr(v_out), _stream(stream)),
            "pyr_prefill_layer_static")
+
+
+def diag_mfma_only(iters, sink, stream=None) -> float:
+    """Launch the MFMA-only diagnostic; returns the floating-point operations of the launch."""
+    fl = ctypes.c_double(0.0)
+    _check(load().pyr_diag_mfma_only(int(iters), _ptr(sink), _stream(stream), ctypes.byref(fl)), "pyr_diag_mfma_only")
+    return float(fl.value)
 
 
 def decode_workspace_bytes(shape: PyrShape, w: int) -> int:
@@ -223,10 +244,10 @@ def to_host_bits(t):
 
 
 def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0, row_weights=None, pos=None):
-    """Upload the arrays of synth.make_inputs, run pyr_prefill_layer (+ pyr_compact on the
-    hidden rows), download everything.  Buffers are allocated with torch; every step of
-    the path runs in the library.  With row_weights (float [w]) and/or pos (int [T]) the
-    call goes through pyr_prefill_layer_ex."""
+    """Upload the arrays of synth.make_inputs, run the layer step through ONE entry point, download
+    everything.  Buffers are allocated with torch; every step of the path runs in the library.
+    With hidden rows the call is pyr_prefill_layer_fused, with row_weights (float [w]) and/or
+    pos (int [T]) but no hidden rows pyr_prefill_layer_ex, else pyr_prefill_layer."""
     import numpy as np
     import torch
     q, k, v = (to_device_bf16(x[n]) for n in ("q", "k", "v"))
@@ -240,7 +261,7 @@ def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0, row_weights=N
     shape = make_shape(B, T, int(lens.max()) if B else 0, Hq, Hkv, d)
     n_kept = int(keep_h.sum())
     ws_bytes = workspace_bytes(shape, w)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    ws = torch.full((ws_bytes,), 0xAB, dtype=torch.uint8, device="cuda")     # the library must not rely on its contents
     out = torch.empty_like(q)
     scores = torch.empty(T, dtype=torch.float32, device="cuda")
     kept = torch.empty(max(n_kept, 1), dtype=torch.int32, device="cuda")
@@ -248,22 +269,23 @@ def prefill_layer_from_numpy(x, w, hidden=None, softmax_scale=0.0, row_weights=N
     k_out = torch.empty((max(n_kept, 1), Hkv, d), dtype=torch.bfloat16, device="cuda")
     v_out = torch.empty_like(k_out)
     res = {}
-    if row_weights is None and pos is None:
+    rw_d = None if row_weights is None else torch.from_numpy(np.ascontiguousarray(row_weights, dtype=np.float32)).cuda()
+    pos_d = None if pos is None else torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).cuda()
+    pos_out = None if pos is None else torch.empty(max(n_kept, 1), dtype=torch.int32, device="cuda")
+    if hidden is not None:                      # everything in one call: pyr_prefill_layer_fused
+        hid = to_device_bf16(hidden)
+        hid_out = torch.empty((max(n_kept, 1), hid.shape[1]), dtype=torch.bfloat16, device="cuda")
+        prefill_layer_fused(q, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, rw_d, hid, hid.shape[1] * 2,
+                            pos_d, out, scores, kept, out_off, k_out, v_out, hid_out, pos_out, ws, ws_bytes)
+        res["hidden_out"] = to_host_bits(hid_out)[:n_kept]
+    elif row_weights is None and pos is None:
         prefill_layer(q, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, out, scores, kept, out_off,
                       k_out, v_out, ws, ws_bytes)
     else:
-        rw_d = None if row_weights is None else torch.from_numpy(np.ascontiguousarray(row_weights, dtype=np.float32)).cuda()
-        pos_d = None if pos is None else torch.from_numpy(np.ascontiguousarray(pos, dtype=np.int32)).cuda()
-        pos_out = None if pos is None else torch.empty(max(n_kept, 1), dtype=torch.int32, device="cuda")
         prefill_layer_ex(q, k, v, off_d, off_h, shape, w, softmax_scale, keep_d, keep_h, rw_d, pos_d, out, scores, kept,
                          out_off, k_out, v_out, pos_out, ws, ws_bytes)
-        if pos is not None:
-            res["pos_out"] = pos_out.cpu().numpy()[:n_kept]
-    if hidden is not None:
-        hid = to_device_bf16(hidden)
-        hid_out = torch.empty((max(n_kept, 1), hid.shape[1]), dtype=torch.bfloat16, device="cuda")
-        compact(hid, hid.shape[1] * 2, kept, n_kept, hid_out)
-        res["hidden_out"] = to_host_bits(hid_out)[:n_kept]
+    if pos is not None:
+        res["pos_out"] = pos_out.cpu().numpy()[:n_kept]
     torch.cuda.synchronize()
     res.update(out=to_host_bits(out), scores=scores.cpu().numpy(), kept_idx=kept.cpu().numpy()[:n_kept].astype(np.int64),
                out_offsets=out_off.cpu().numpy(), k_out=to_host_bits(k_out)[:n_kept], v_out=to_host_bits(v_out)[:n_kept],

@@ -17,7 +17,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct BatchInfo {
     int32_t uniform_len;    // common length if all sequences have one (> 0), else 0
-    int32_t max_len;
+    int32_t max_len, min_len;
 };
 
 int check_shape(const pyr_shape* s) {
@@ -35,12 +35,13 @@ int check_shape(const pyr_shape* s) {
 int check_offsets(const int32_t* off, int32_t n_seqs, int32_t total, int32_t max_len_claimed, BatchInfo* info) {
     if (off == nullptr) return PYR_ERR_NULL;
     if (off[0] != 0) return PYR_ERR_OFFSETS;
-    int32_t max_len = 0, first = n_seqs > 0 ? off[1] - off[0] : 0;
+    int32_t max_len = 0, min_len = 0x7fffffff, first = n_seqs > 0 ? off[1] - off[0] : 0;
     bool uniform = n_seqs > 0;
     for (int32_t b = 0; b < n_seqs; ++b) {
         if (off[b + 1] < off[b]) return PYR_ERR_OFFSETS;
         const int32_t len = off[b + 1] - off[b];
         if (len > max_len) max_len = len;
+        if (len < min_len) min_len = len;
         if (len != first) uniform = false;
     }
     if (off[n_seqs] != total) return PYR_ERR_OFFSETS;
@@ -48,6 +49,7 @@ int check_offsets(const int32_t* off, int32_t n_seqs, int32_t total, int32_t max
     if (info != nullptr) {
         info->uniform_len = (uniform && first > 0) ? first : 0;
         info->max_len = max_len;
+        info->min_len = n_seqs > 0 ? min_len : 0;
     }
     return PYR_OK;
 }
@@ -114,7 +116,7 @@ int pyr_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out) {
     if (rc != PYR_OK) return rc;
     if (w < 1) return PYR_ERR_SHAPE;
     *bytes_out = align_up((size_t)shape->total_tokens * shape->n_q_heads * sizeof(float)) +
-                 align_up(((size_t)shape->n_seqs + 1) * sizeof(int32_t));
+                 align_up(((size_t)shape->n_seqs + 1) * sizeof(int32_t)) + align_up(pyr::score_tail_bytes(*shape));
     return PYR_OK;
 }
 
@@ -162,7 +164,7 @@ int pyr_attention(const void* q, const void* k, const void* v,
     if (rc != PYR_OK) return rc;
     if (info.uniform_len == 0 && shape->total_tokens > 0 && tile_map == nullptr) return PYR_ERR_WORKSPACE;
     return pyr::launch_attention(q, k, v, seq_offsets_dev, seq_offsets_host, *shape, info.uniform_len,
-                                 scale_log2(softmax_scale, shape->head_dim), out, lse, tile_map,
+                                 scale_log2(softmax_scale, shape->head_dim), out, lse, tile_map, nullptr, 0,
                                  (hipStream_t)stream);
 }
 
@@ -257,14 +259,32 @@ int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
                       void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
                       void* k_out, void* v_out, int32_t* pos_out,
                       void* workspace, size_t workspace_bytes, void* stream) {
+    return pyr_prefill_layer_fused(q, k, v, seq_offsets_dev, seq_offsets_host, shape, w, softmax_scale, keep_len_dev,
+                                   keep_len_host, row_weights_dev, nullptr, 0, pos, out, scores, kept_idx, out_offsets_dev,
+                                   k_out, v_out, nullptr, pos_out, workspace, workspace_bytes, stream);
+}
+
+int pyr_prefill_layer_fused(const void* q, const void* k, const void* v,
+                      const int32_t* seq_offsets_dev, const int32_t* seq_offsets_host,
+                      const pyr_shape* shape, int32_t w, float softmax_scale,
+                      const int32_t* keep_len_dev, const int32_t* keep_len_host,
+                      const float* row_weights_dev, const void* hidden, size_t hidden_row_bytes, const int32_t* pos,
+                      void* out, float* scores, int32_t* kept_idx, int32_t* out_offsets_dev,
+                      void* k_out, void* v_out, void* hidden_out, int32_t* pos_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);
     if (rc != PYR_OK) return rc;
     if (w < 1) return PYR_ERR_SHAPE;
     if (!q || !k || !v || !out || !scores || !kept_idx || !out_offsets_dev || !seq_offsets_dev ||
         !seq_offsets_host || !keep_len_dev || !keep_len_host)
         return PYR_ERR_NULL;
-    if ((k_out == nullptr) != (v_out == nullptr) || (pos == nullptr) != (pos_out == nullptr)) return PYR_ERR_NULL;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(k_out) || !aligned16(v_out))
+    if ((k_out == nullptr) != (v_out == nullptr) || (pos == nullptr) != (pos_out == nullptr) ||
+        (hidden == nullptr) != (hidden_out == nullptr))
+        return PYR_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(k_out) || !aligned16(v_out) ||
+        !aligned16(hidden) || !aligned16(hidden_out))
+        return PYR_ERR_UNSUPPORTED;
+    if (hidden != nullptr && (hidden_row_bytes == 0 || hidden_row_bytes % 16 != 0 || hidden_row_bytes / 16 > 0x7fffffff))
         return PYR_ERR_UNSUPPORTED;
     BatchInfo info;
     rc = check_offsets(seq_offsets_host, shape->n_seqs, shape->total_tokens, shape->max_seqlen, &info);
@@ -277,27 +297,44 @@ int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
     if (rc != PYR_OK) return rc;
     if (workspace == nullptr || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return PYR_ERR_WORKSPACE;
 
+    // workspace: row statistics | tile map | the score pass's counters and partial sums
     float* lse = (float*)workspace;
-    int32_t* tile_map =
-        (int32_t*)((char*)workspace + align_up((size_t)shape->total_tokens * shape->n_q_heads * sizeof(float)));
+    char* at = (char*)workspace + align_up((size_t)shape->total_tokens * shape->n_q_heads * sizeof(float));
+    int32_t* tile_map = (int32_t*)at;
+    at += align_up(((size_t)shape->n_seqs + 1) * sizeof(int32_t));
+    void* tail_ws = at;
     hipStream_t st = (hipStream_t)stream;
     const float c = scale_log2(softmax_scale, shape->head_dim);
     pyr_shape s = *shape;
     s.max_seqlen = info.max_len;
 
-    rc = pyr::launch_attention(q, k, v, seq_offsets_dev, seq_offsets_host, s, info.uniform_len, c, out, lse, tile_map, st);
+    // three launches (four for a ragged batch: the tile map): attention, which also clears the counters of the
+    // next one; the score pass, whose last workgroup per sequence selects; one gather for everything
+    rc = pyr::launch_attention(q, k, v, seq_offsets_dev, seq_offsets_host, s, info.uniform_len, c, out, lse, tile_map,
+                               (int32_t*)tail_ws, pyr::score_tail_counters(s), st);
     if (rc != PYR_OK) return rc;
-    rc = pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, c, row_weights_dev, scores, st);
+    bool selected = false;
+    rc = pyr::launch_score_select(q, k, lse, seq_offsets_dev, s, info.min_len, w, c, row_weights_dev, scores, keep_len_dev,
+                                  kept_idx, out_offsets_dev, tail_ws, &selected, st);
     if (rc != PYR_OK) return rc;
-    rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
-                            out_offsets_dev, st);
-    if (rc != PYR_OK) return rc;
-    if (k_out != nullptr && total_kept > 0) {
-        const size_t row_bytes = (size_t)shape->n_kv_heads * shape->head_dim * 2;
-        rc = pyr::launch_gather(k, k_out, v, v_out, row_bytes, kept_idx, total_kept, st);
+    if (!selected) {
+        rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
+                                out_offsets_dev, st);
         if (rc != PYR_OK) return rc;
     }
-    if (pos != nullptr && total_kept > 0) rc = pyr::launch_gather_positions(pos, kept_idx, total_kept, pos_out, st);
+    if (total_kept > 0) {
+        const void* srcs[3];
+        void* dsts[3];
+        size_t rows[3];
+        int n = 0;
+        if (k_out != nullptr) {
+            const size_t kv_row = (size_t)shape->n_kv_heads * shape->head_dim * 2;
+            srcs[n] = k; dsts[n] = k_out; rows[n++] = kv_row;
+            srcs[n] = v; dsts[n] = v_out; rows[n++] = kv_row;
+        }
+        if (hidden != nullptr) { srcs[n] = hidden; dsts[n] = hidden_out; rows[n++] = hidden_row_bytes; }
+        rc = pyr::launch_gather_multi(n, srcs, dsts, rows, pos, pos_out, kept_idx, total_kept, st);
+    }
     return rc;
 }
 

@@ -173,7 +173,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ seq_offsets, const int32_t* __restrict__ item_map,
     int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t uniform_len, int32_t xcds,
-    int32_t items_per_xcd, int32_t first_wave_slots, float c, uint16_t* __restrict__ out, float* __restrict__ lse) {
+    int32_t items_per_xcd, int32_t first_wave_slots, float c, uint16_t* __restrict__ out, float* __restrict__ lse,
+    int32_t* __restrict__ zero_ptr, int32_t zero_count) {
     using T = Tile<D, kNW>;
     constexpr int kBM = kNW * 32;                 // query positions per segment
     constexpr int NS = D / 16;                    // MFMAs per group = k-steps of QK^T = V fragments of a half
@@ -190,6 +191,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // A service to the kernels that follow on the stream: their arrival counters start at zero.
+    if (blockIdx.x == 0)
+        for (int i = tid; i < zero_count; i += kNW * 64) zero_ptr[i] = 0;
     // 32-row block of this wavefront.  Eight wavefronts: SIMD s owns blocks s and 7-s.  Four: one wavefront per
     // SIMD, and the second workgroup of a compute unit (slot >= first_wave_slots) deals the blocks the other
     // way round, so that the two wavefronts sharing a SIMD again own blocks s and 3-s.
@@ -810,7 +814,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void attention_kernel(
 template <int D, int kNW>
 int launch_attention_d(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
                        const int32_t* seq_offsets_host, const pyr_shape& s, int32_t uniform_len, float c,
-                       void* out, float* lse, int32_t* item_map, hipStream_t stream) {
+                       void* out, float* lse, int32_t* item_map, int32_t* zero_ptr, int32_t zero_count,
+                       hipStream_t stream) {
     auto kern = attention_kernel<D, kNW>;
     using T = Tile<D, kNW>;
     constexpr int kBM = kNW * 32;
@@ -822,7 +827,6 @@ int launch_attention_d(const void* q, const void* k, const void* v, const int32_
     if (total_items * s.n_q_heads >= (1ll << 31)) return PYR_ERR_UNSUPPORTED;
     DeviceInfo dev;
     if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
-    if (const char* e = getenv("PYR_ATTN_CUS")) dev.compute_units = atoi(e);      // EXPERIMENT
     if (uniform_len == 0) {
         hipLaunchKernelGGL(item_map_kernel, dim3(1), dim3(1024), 0, stream, seq_offsets_dev, s.n_seqs, (int32_t)kBM, item_map);
         if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
@@ -839,7 +843,7 @@ int launch_attention_d(const void* q, const void* k, const void* v, const int32_
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kNW * 64), T::kLdsBytes, stream,
                        (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, seq_offsets_dev,
                        (const int32_t*)item_map, s.n_seqs, s.n_q_heads, s.n_kv_heads, uniform_len, xcds,
-                       items_per_xcd, first_wave_slots, c, (uint16_t*)out, lse);
+                       items_per_xcd, first_wave_slots, c, (uint16_t*)out, lse, zero_ptr, zero_count);
     return check_launch();
 }
 
@@ -847,17 +851,25 @@ int launch_attention_d(const void* q, const void* k, const void* v, const int32_
 
 int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
                      const int32_t* seq_offsets_host, const pyr_shape& shape, int32_t uniform_len, float scale_log2,
-                     void* out, float* lse, int32_t* item_map, hipStream_t stream) {
-    const char* env = getenv("PYR_ATTN_NW");         // EXPERIMENT: wavefronts per workgroup
-    const int nw = env ? atoi(env) : 8;
+                     void* out, float* lse, int32_t* item_map, int32_t* zero_ptr, int32_t zero_count,
+                     hipStream_t stream) {
+    // Segments of 256 query rows (eight wavefronts) make the most of every K/V tile brought into LDS; when they
+    // leave compute units without work (small batches), segments of 128 rows (four wavefronts) double the number
+    // of work items.
+    DeviceInfo dev;
+    if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
+    long long items256 = 0;
+    for (int32_t b = 0; b < shape.n_seqs; ++b) items256 += items_of(seq_offsets_host[b + 1] - seq_offsets_host[b], 256);
+    const bool small = items256 * shape.n_q_heads < dev.compute_units;
     if (shape.head_dim == 128)
-        return launch_attention_d<128, 8>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
-                                          out, lse, item_map, stream);
-    if (nw == 4)
-        return launch_attention_d<64, 4>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
-                                         out, lse, item_map, stream);
-    return launch_attention_d<64, 8>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
-                                     out, lse, item_map, stream);
+        return small ? launch_attention_d<128, 4>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                                  out, lse, item_map, zero_ptr, zero_count, stream)
+                     : launch_attention_d<128, 8>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                                  out, lse, item_map, zero_ptr, zero_count, stream);
+    return small ? launch_attention_d<64, 4>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                             out, lse, item_map, zero_ptr, zero_count, stream)
+                 : launch_attention_d<64, 8>(q, k, v, seq_offsets_dev, seq_offsets_host, shape, uniform_len, scale_log2,
+                                             out, lse, item_map, zero_ptr, zero_count, stream);
 }
 
 }  // namespace pyr

@@ -42,6 +42,51 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     }
 }
 
+// Several sources gathered with one index list in ONE launch (K, V, the hidden rows, the position ids): at small
+// batch every launch costs about as much as the rows it moves (Appendix A.1 is about exactly this regime).
+// blockIdx.y picks the source; the last y, if pos is given, gathers the 4-byte position ids.
+struct GatherSources {
+    const u32x4* src[3];
+    u32x4* dst[3];
+    int32_t chunks[3];                 // 16-byte chunks per row
+    int32_t n;
+    const int32_t* pos;
+    int32_t* pos_out;
+};
+
+__global__ __launch_bounds__(kThreads) void gather_multi_kernel(GatherSources g, const int32_t* __restrict__ kept_idx,
+                                                                int64_t n_rows) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int y = blockIdx.y;
+    if (y >= g.n) {                    // position ids
+        for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < n_rows; j += (int64_t)gridDim.x * kThreads)
+            g.pos_out[j] = g.pos[kept_idx[j]];
+        return;
+    }
+    const u32x4* __restrict__ src = y == 0 ? g.src[0] : y == 1 ? g.src[1] : g.src[2];
+    u32x4* __restrict__ dst = y == 0 ? g.dst[0] : y == 1 ? g.dst[1] : g.dst[2];
+    const int32_t chunks_per_row = y == 0 ? g.chunks[0] : y == 1 ? g.chunks[1] : g.chunks[2];
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    for (int64_t j = (int64_t)blockIdx.x * kWavesPerBlock + wave; j < n_rows; j += wave_stride) {
+        const int64_t from = (int64_t)kept_idx[j] * chunks_per_row;
+        const int64_t to = j * chunks_per_row;
+        for (int c0 = 0; c0 < chunks_per_row; c0 += 64 * kUnroll) {
+            u32x4 buf[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < chunks_per_row) buf[u] = __builtin_nontemporal_load(src + from + c);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < chunks_per_row) __builtin_nontemporal_store(buf[u], dst + to + c);
+            }
+        }
+    }
+}
+
 // Position ids of the kept tokens (Appendix A.2: the survivors keep the position encodings
 // they had; the ids are gathered with the same index as K and V): pos_out[j] = pos[kept_idx[j]].
 __global__ __launch_bounds__(256) void gather_positions_kernel(const int32_t* __restrict__ pos,
@@ -59,6 +104,26 @@ int launch_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t
     int64_t blocks = (n_kept + 255) / 256;
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(gather_positions_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, pos, kept_idx, n_kept, pos_out);
+    return check_launch();
+}
+
+int launch_gather_multi(int n, const void* const* srcs, void* const* dsts, const size_t* row_bytes, const int32_t* pos,
+                        int32_t* pos_out, const int32_t* kept_idx, int64_t n_kept, hipStream_t stream) {
+    if (n_kept == 0 || (n == 0 && pos == nullptr)) return PYR_OK;
+    GatherSources g{};
+    for (int i = 0; i < n; ++i) {
+        g.src[i] = (const u32x4*)srcs[i];
+        g.dst[i] = (u32x4*)dsts[i];
+        g.chunks[i] = (int32_t)(row_bytes[i] / 16);
+    }
+    g.n = n;
+    g.pos = pos;
+    g.pos_out = pos_out;
+    int64_t blocks = (n_kept + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t cap = 256 * 64;
+    if (blocks > cap) blocks = cap;
+    dim3 grid((unsigned)blocks, (unsigned)(n + (pos != nullptr ? 1 : 0)), 1);
+    hipLaunchKernelGGL(gather_multi_kernel, grid, dim3(kThreads), 0, stream, g, kept_idx, n_kept);
     return check_launch();
 }
 

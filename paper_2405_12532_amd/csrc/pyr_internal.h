@@ -23,18 +23,34 @@ constexpr float kLog2e = 1.4426950408889634f;
 int launch_gather(const void* src0, void* dst0, const void* src1, void* dst1, size_t row_bytes,
                   const int32_t* kept_idx, int64_t n_kept, hipStream_t stream);
 
+// up to three row sources (row_bytes[i] a multiple of 16) and, if pos != nullptr, the position ids, in one launch
+int launch_gather_multi(int n, const void* const* srcs, void* const* dsts, const size_t* row_bytes, const int32_t* pos,
+                        int32_t* pos_out, const int32_t* kept_idx, int64_t n_kept, hipStream_t stream);
+
 int launch_select(const float* scores, const int32_t* seq_offsets_dev, const int32_t* keep_len_dev,
                   int32_t n_seqs, int32_t max_seqlen, int32_t w, int32_t* kept_idx, int32_t* out_offsets_dev,
                   hipStream_t stream);
 
 int launch_attention(const void* q, const void* k, const void* v, const int32_t* seq_offsets_dev,
                      const int32_t* seq_offsets_host, const pyr_shape& shape, int32_t uniform_len, float scale_log2,
-                     void* out, float* lse, int32_t* item_map, hipStream_t stream);
+                     void* out, float* lse, int32_t* item_map, int32_t* zero_ptr, int32_t zero_count,
+                     hipStream_t stream);     // zero_ptr[0 .. zero_count) is cleared by the kernel (may be nullptr, 0)
 
 // row_weights: device [w] or nullptr (uniform)
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
                  const pyr_shape& shape, int32_t w, float scale_log2, const float* row_weights, float* scores,
                  hipStream_t stream);
+
+// The score pass with its small-batch extras (see score.hip): KV heads split over several workgroups per key block
+// when the grid is small, and the top-k selection run by the workgroup that completes a sequence (*selected tells
+// whether it was; if not, launch_select is still to be called).  tail_ws: score_tail_bytes() bytes whose first
+// score_tail_counters() int32 are zero at launch (the kernel leaves them zero).
+size_t score_tail_bytes(const pyr_shape& shape);
+int32_t score_tail_counters(const pyr_shape& shape);
+int launch_score_select(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
+                        const pyr_shape& shape, int32_t min_seqlen, int32_t w, float scale_log2,
+                        const float* row_weights, float* scores, const int32_t* keep_len_dev, int32_t* kept_idx,
+                        int32_t* out_offsets_dev, void* tail_ws, bool* selected, hipStream_t stream);
 
 // Generation phase: the same scores from the window's own query buffer q_win [B, w, Hq, d]
 // (right-aligned), three launches: per-block row statistics -> part, folded into lse_win

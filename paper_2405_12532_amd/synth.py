@@ -86,7 +86,8 @@ def _ragged_lengths(n, lo, hi, seed):
 
 def workload(name: str) -> Workload:
     """The five synthetic configurations of this build, by name ("cfg1" .. "cfg5"),
-    plus "64x2k": the first layer of cfg3, the shape throughput is quoted on."""
+    plus "64x2k": the first layer of cfg3, the shape throughput is quoted on, and
+    "1x2k" / "1x8k": a single prompt on the same layer shape (small-batch timing)."""
     if name == "cfg1":
         return Workload("cfg1", (256,), 8, 8, 64, 16, 1, 2, keep_fixed=128, seed=BASE_SEED + 1)
     if name == "cfg2":
@@ -94,6 +95,9 @@ def workload(name: str) -> Workload:
     if name in ("cfg3", "64x2k"):
         return Workload(name, (2048,) * 64, 32, 32, 128, 64, 93, 100, keep_floor=192, heavy_frac=0.10,
                         hidden_dim=4096, seed=BASE_SEED + 3, n_layers=32 if name == "cfg3" else 1)
+    if name in ("1x2k", "1x8k"):            # one prompt on the 7B-shaped layer: the small-batch regime of Appendix A.1
+        return Workload(name, (2048 if name == "1x2k" else 8192,), 32, 32, 128, 64, 93, 100, keep_floor=192,
+                        heavy_frac=0.10, hidden_dim=4096, seed=BASE_SEED + 6)
     if name == "cfg4":
         lens = _ragged_lengths(32, 512, 8192, BASE_SEED + 4)
         return Workload("cfg4", lens, 40, 40, 128, 64, 6, 10, heavy_frac=0.10, seed=BASE_SEED + 4)

@@ -215,6 +215,9 @@ def main():
     ap.add_argument("--workload", default="64x2k", help="64x2k (default), cfg1, cfg2, cfg4, cfg5, 1x2k, 1x8k")
     ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences the CPU oracle is timed on (0: skip)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step (for profiler runs)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one device-to-device copy of 1 GiB with torch (a copy of known size that is not this "
+                         "library's, to scale the profiler's FETCH_SIZE / WRITE_SIZE counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -279,6 +282,14 @@ def main():
             "traffic": traffic.get("gather"), "bytes_per_step": compact_bytes + select_bytes},
         "score_tflops": score_flops(wl.seq_lens, Hq, d, wl.w) / (kernel_ms["score"] * 1e-3) / 1e12,
     }
+
+    if args.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_extras:
         # ---- ceilings of this very GPU, beside the published peaks

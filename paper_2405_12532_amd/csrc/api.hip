@@ -27,6 +27,7 @@ int check_shape(const pyr_shape* s) {
     if (s->max_seqlen > s->total_tokens) return PYR_ERR_SHAPE;
     if (s->head_dim != 64 && s->head_dim != 128) return PYR_ERR_UNSUPPORTED;
     if (s->n_q_heads % s->n_kv_heads != 0) return PYR_ERR_UNSUPPORTED;
+    if (s->n_q_heads > 32767) return PYR_ERR_UNSUPPORTED;      // head numbers are packed into 16 bits, row strides into 24
     // the kernels index elements of q with 64-bit offsets, but row numbers stay 32-bit
     if ((int64_t)s->total_tokens * s->n_q_heads >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
     return PYR_OK;

@@ -168,7 +168,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 #pragma unroll
         for (int i = 0; i < kNK; ++i) {
             const int row = kRowsPerLoad * i + ld_row;
-            lds_dma(base, (uint32_t)min(row, lim) * k_row_bytes + 16 * (ld_chunk ^ (row & (kChunks - 1))), kt + 1024 * i,
+            // (24-bit multiply: full rate, where the 32-bit one takes four times as long; rows and strides are far below 2^24)
+            lds_dma(base, __umul24((uint32_t)min(row, lim), k_row_bytes) + 16 * (ld_chunk ^ (row & (kChunks - 1))), kt + 1024 * i,
                     false);
         }
     };
@@ -181,12 +182,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 #pragma unroll
         for (int i = 0; i < kNQ; ++i) {
             const int row = kRowsPerLoad * i + ld_row;
-            lds_dma(base, (uint32_t)min(row, last_row) * q_row_bytes + 16 * (ld_chunk ^ (row & (kChunks - 1))),
+            lds_dma(base, __umul24((uint32_t)min(row, last_row), q_row_bytes) + 16 * (ld_chunk ^ (row & (kChunks - 1))),
                     qt + 1024 * i, false);
         }
         if (kMode != kStats)
             lds_dma((const char*)(lse + (size_t)(q_row_base + 32 * rb) * n_q_heads + h),
-                    (uint32_t)min(li, last_row) * n_q_heads * 4, lt, true);
+                    __umul24((uint32_t)min(li, last_row), (uint32_t)n_q_heads * 4), lt, true);
         if (kWeighted) lds_dma((const char*)(row_weights + (w - L) + 32 * rb), (uint32_t)min(li, last_row) * 4, wt, true);
     };
 

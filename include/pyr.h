@@ -289,7 +289,7 @@ PYR_API int pyr_prefill_layer_fused(const void* q, const void* k, const void* v,
  *                      must not overlap k)
  *   workspace          dev, >= pyr_decode_workspace_bytes(), 256-byte aligned
  * Five launches on the stream: per-key-block softmax statistics of the window rows, their
- * fold into row denominators, the score pass, the selection, the gathers.  The attention
+ * fold into row denominators, the score pass, the selection, one gather for K, V and position ids.  The attention
  * output of the new token itself is not computed here.
  */
 PYR_API int pyr_decode_workspace_bytes(const pyr_shape* shape, int32_t w, size_t* bytes_out);

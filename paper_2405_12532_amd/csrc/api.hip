@@ -407,12 +407,13 @@ int pyr_decode_update(const void* q_win, const void* k, const void* v,
     rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
                             out_offsets_dev, st);
     if (rc != PYR_OK) return rc;
-    if (k_out != nullptr && total_kept > 0) {
+    if (total_kept > 0) {                             // K, V and the position ids in one launch
         const size_t row_bytes = (size_t)shape->n_kv_heads * shape->head_dim * 2;
-        rc = pyr::launch_gather(k, k_out, v, v_out, row_bytes, kept_idx, total_kept, st);
-        if (rc != PYR_OK) return rc;
+        const void* srcs[2] = {k, v};
+        void* dsts[2] = {k_out, v_out};
+        const size_t rows[2] = {row_bytes, row_bytes};
+        rc = pyr::launch_gather_multi(k_out != nullptr ? 2 : 0, srcs, dsts, rows, pos, pos_out, kept_idx, total_kept, st);
     }
-    if (pos != nullptr && total_kept > 0) rc = pyr::launch_gather_positions(pos, kept_idx, total_kept, pos_out, st);
     return rc;
 }
 

@@ -124,3 +124,49 @@ def test_fused_step_twice_on_one_workspace(lib):
     for r in res[1:]:
         assert np.array_equal(r[0], res[0][0]) and np.array_equal(r[1], res[0][1]) and np.array_equal(r[2], res[0][2])
     assert (res[0][1] >= 0).all()
+
+
+def test_static_step_replays_from_a_hip_graph(lib):
+    """The step that allocates nothing (pyr_prefill_layer_static) captured into a HIP graph: three replays, with eager
+    work of the same library and synchronisations in between, each equal to the eager result."""
+    wl = synth.shrunk(synth.workload("cfg2"), (700, 300), n_q_heads=8, n_kv_heads=8, head_dim=64, w=32, hidden_dim=0)
+    x = parity.inputs(wl, lib, want_hidden=False)
+    q, k, v = (lib.to_device_bf16(x[n]) for n in ("q", "k", "v"))
+    T, Hq, d = q.shape
+    off_h = torch.from_numpy(np.ascontiguousarray(x["seq_offsets"], dtype=np.int32))
+    keep_h = torch.from_numpy(np.ascontiguousarray(x["keep_len"], dtype=np.int32))
+    off_d, keep_d = off_h.cuda(), keep_h.cuda()
+    n_kept = int(keep_h.sum())
+    shape = lib.make_shape(2, T, 700, Hq, Hq, d)
+    out = torch.empty_like(q)
+    scores = torch.empty(T, dtype=torch.float32, device="cuda")
+    kept = torch.empty(n_kept, dtype=torch.int32, device="cuda")
+    out_off = torch.empty(3, dtype=torch.int32, device="cuda")
+    k_out = torch.empty((n_kept, Hq, d), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.empty_like(k_out)
+
+    def step():
+        lib.prefill_layer_static(q, k, v, off_d, off_h, shape, wl.w, 0.0, keep_d, keep_h, out, scores, kept, out_off, k_out,
+                                 v_out)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (out, scores, kept, out_off, k_out, v_out)]
+
+    step()                                        # eager: also does the once-per-device set-up outside the capture
+    ref = snapshot()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        for t in (out, scores, k_out, v_out):
+            t.zero_()
+        kept.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        got = snapshot()
+        for a, b in zip(got, ref):
+            assert torch.equal(a.view(torch.uint8) if a.dtype == torch.bfloat16 else a,
+                               b.view(torch.uint8) if b.dtype == torch.bfloat16 else b), f"replay {rep}"
+        step()                                    # eager work of the library between the replays
+        torch.cuda.synchronize()

@@ -312,14 +312,32 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         copy_gbs = 10 * 2.0 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del src, dst
+        del dst
+        isink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        read_gbs = {}
+        for name, k_layout in (("consecutive", 0), ("k_layout", 1)):
+            pyr.diag_read_stream(src, src.numel(), k_layout, isink)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(10):
+                pyr.diag_read_stream(src, src.numel(), k_layout, isink)
+            e1.record()
+            torch.cuda.synchronize()
+            read_gbs[name] = 10 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src
+        k_bytes = 2.0 * T * Hkv * d
         line["measured_ceilings"] = {
             "mfma_only_bf16_TFLOPs": mfma_tflops, "published_bf16_TFLOPs": PEAK_BF16_TFLOPS,
             "attention_frac_of_measured_mfma": att_tflops / mfma_tflops,
             "copy_GBs_read_plus_write": copy_gbs, "published_hbm_GBs": PEAK_HBM_GBS,
             "gather_frac_of_measured_copy": compact_bytes / (gather_ms * 1e-3) / 1e9 / copy_gbs,
+            "read_only_GBs": read_gbs["consecutive"], "read_only_k_layout_GBs": read_gbs["k_layout"],
+            "score_pass_k_read_at_that_rate_ms": k_bytes / read_gbs["k_layout"] / 1e6,
+            "score_pass_ms": kernel_ms["score"],
             "how": "MFMA: pyr_diag_mfma_only, 64000 v_mfma_f32_32x32x16_bf16 per wavefront, 2 wavefronts per SIMD on every "
-                   "compute unit; copy: torch copy_ of 1 GiB device to device, 10 times"}
+                   "compute unit; copy: torch copy_ of 1 GiB device to device, 10 times; read only: pyr_diag_read_stream over 1 GiB, "
+                   "10 times (LDS-direct loads as the score pass issues them for K, consecutive tiles or K's strided "
+                   "layout at 32 heads of 128), against which the score pass's own K read is priced"}
 
         # ---- the optional parts of the step, timed on their own
         rw = torch.linspace(0.25, 1.0, wl.w, dtype=torch.float32, device="cuda")

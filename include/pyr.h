@@ -312,6 +312,20 @@ PYR_API int pyr_decode_update(const void* q_win, const void* k, const void* v,
  */
 PYR_API int pyr_diag_mfma_only(int32_t iters, float* sink_dev, void* stream, double* flops_out);
 
+/*
+ * Diagnostic for the benchmark report, not part of the method: a launch that only reads `bytes` of device
+ * memory with the LDS-direct loads the score pass uses for K (16 KB tiles, one in flight per wavefront, six
+ * wavefronts per compute unit) and discards them, so that the read rate this very GPU sustains can be printed
+ * beside the published HBM peak.
+ *   data_dev           dev, `bytes` readable bytes, 16-byte aligned
+ *   bytes              a positive multiple of 524288, below 2^50
+ *   k_layout           0: consecutive tiles; != 0: tiles of 64 rows x 256 bytes, rows 8192 bytes apart (one head of
+ *                      64 tokens of a [T, 32, 128] bf16 K)
+ *   sink_dev           dev, one int32 (never written in practice)
+ * Errors: PYR_ERR_NULL, PYR_ERR_SHAPE (bytes), PYR_ERR_LAUNCH.
+ */
+PYR_API int pyr_diag_read_stream(const void* data_dev, size_t bytes, int32_t k_layout, int32_t* sink_dev, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,6 +53,7 @@ _SIGNATURES = {
     "pyr_prefill_layer": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.POINTER(PyrShape), _I32, _F32, _VP, _VP,
                                          _VP, _VP, _VP, _VP, _VP, _VP, _VP, _SZ, _VP]),
     "pyr_diag_mfma_only": (ctypes.c_int, [_I32, _VP, _VP, ctypes.POINTER(ctypes.c_double)]),
+    "pyr_diag_read_stream": (ctypes.c_int, [_VP, _SZ, _I32, _VP, _VP]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -210,6 +211,12 @@ def diag_mfma_only(iters, sink, stream=None) -> float:
     fl = ctypes.c_double(0.0)
     _check(load().pyr_diag_mfma_only(int(iters), _ptr(sink), _stream(stream), ctypes.byref(fl)), "pyr_diag_mfma_only")
     return float(fl.value)
+
+
+def diag_read_stream(data, nbytes, k_layout, sink, stream=None) -> None:
+    """Launch the read-only diagnostic over the first nbytes of data (LDS-direct loads, discarded)."""
+    _check(load().pyr_diag_read_stream(_ptr(data), int(nbytes), int(bool(k_layout)), _ptr(sink), _stream(stream)),
+           "pyr_diag_read_stream")
 
 
 def decode_workspace_bytes(shape: PyrShape, w: int) -> int:

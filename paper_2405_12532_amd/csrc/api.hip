@@ -183,7 +183,7 @@ int pyr_score_weighted(const void* q, const void* k, const float* lse,
     if (rc != PYR_OK) return rc;
     pyr_shape s = *shape;
     s.max_seqlen = info.max_len;
-    return pyr::launch_score(q, k, lse, seq_offsets_dev, s, w, scale_log2(softmax_scale, shape->head_dim),
+    return pyr::launch_score(q, k, lse, seq_offsets_dev, s, info.min_len, w, scale_log2(softmax_scale, shape->head_dim),
                              row_weights_dev, scores, (hipStream_t)stream);
 }
 

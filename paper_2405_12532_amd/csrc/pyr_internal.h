@@ -36,10 +36,10 @@ int launch_attention(const void* q, const void* k, const void* v, const int32_t*
                      void* out, float* lse, int32_t* item_map, int32_t* zero_ptr, int32_t zero_count,
                      hipStream_t stream);     // zero_ptr[0 .. zero_count) is cleared by the kernel (may be nullptr, 0)
 
-// row_weights: device [w] or nullptr (uniform)
+// row_weights: device [w] or nullptr (uniform); min_seqlen: the shortest sequence (0 if not known)
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
-                 const pyr_shape& shape, int32_t w, float scale_log2, const float* row_weights, float* scores,
-                 hipStream_t stream);
+                 const pyr_shape& shape, int32_t min_seqlen, int32_t w, float scale_log2, const float* row_weights,
+                 float* scores, hipStream_t stream);
 
 // The score pass with its small-batch extras (see score.hip): KV heads split over several workgroups per key block
 // when the grid is small, and the top-k selection run by the workgroup that completes a sequence (*selected tells

@@ -94,8 +94,8 @@ template <int D, int kMode>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
     const int32_t* __restrict__ seq_offsets, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t w,
-    int32_t blocks_per_seq, int32_t q_window, float c, const float* __restrict__ row_weights,
-    float* __restrict__ scores, float2* __restrict__ part, ScoreTail tail) {
+    int32_t blocks_per_seq, int32_t chunk_blocks, int32_t xcds, int32_t q_window, float c,
+    const float* __restrict__ row_weights, float* __restrict__ scores, float2* __restrict__ part, ScoreTail tail) {
     constexpr bool kWeighted = kMode == kScoresWeighted;
     constexpr int kKSteps = D / 16;
     constexpr int kChunks = D / 8;                  // 16-byte chunks per row
@@ -112,22 +112,29 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 31, gl = lane >> 5;
-    const int b = blockIdx.x / blocks_per_seq;
+    // Workgroup -> (sequence, key block).  Consecutive workgroup ids go to consecutive XCDs; a chunk of
+    // chunk_blocks key blocks of one sequence stays on one XCD, so that the window's Q rows, which every key
+    // block of the sequence re-reads, are found in that XCD's L2.
+    const int wg_slot = (int)blockIdx.x / xcds;
+    const int chunk = (wg_slot / chunk_blocks) * xcds + (int)blockIdx.x % xcds;
+    const int chunks_per_seq = (blocks_per_seq + chunk_blocks - 1) / chunk_blocks;
+    const int b = chunk / chunks_per_seq;
+    const int key_block = (chunk % chunks_per_seq) * chunk_blocks + wg_slot % chunk_blocks;
+    if (b >= n_seqs || key_block >= blocks_per_seq) return;      // (uniform over the workgroup, like the next one)
     const int row0 = seq_offsets[b];
     const int S = seq_offsets[b + 1] - row0;
-    const int key_base = (blockIdx.x % blocks_per_seq) * kKeysPerBlock;
-    if (key_base >= S) return;                        // uniform over the workgroup
+    const int key_base = key_block * kKeysPerBlock;
+    if (key_base >= S) return;
     const int L = min(w, S);
     const int first_row = S - L;                      // local position of the first window row
     const int q_row_base = q_window ? b * w + (w - L) : row0 + first_row;   // row of q / lse holding the first window row
-    const int key_block = blockIdx.x % blocks_per_seq;
     const int n_row_blocks = (L + 31) / 32;
     const int group = n_q_heads / n_kv_heads;
     const int n_steps = group * n_row_blocks;         // per KV head
     // this workgroup's share of the KV heads (all of them unless the launcher split them over gridDim.y), halved
     // between the two wavefronts
     const int wg_heads = n_kv_heads / (int)gridDim.y, wg_first = (int)blockIdx.y * wg_heads;
-    const int kvh_begin = wg_first + wave * wg_heads / kWavesPerBlock, kvh_end = wg_first + (wave + 1) * wg_heads / kWavesPerBlock;
+    const int kvh_begin = wg_first + wave, kvh_end = wg_first + wg_heads;     // interleaved: the wavefronts read adjacent heads at the same time
 
     float acc[2][16];
 #pragma unroll
@@ -202,8 +209,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         issue_q(kvh_begin, 0);
     }
     // Outstanding loads at the top of a head: its K tile (oldest), then its first step's rows.
-    for (int kvh = kvh_begin; kvh < kvh_end; ++kvh) {
-        const bool has_next = kvh + 1 < kvh_end;
+    for (int kvh = kvh_begin; kvh < kvh_end; kvh += kWavesPerBlock) {
+        const bool has_next = kvh + kWavesPerBlock < kvh_end;
         wait_loads<kStepLoads>();                     // the K tile has landed
         bf16x8 kf[2][kKSteps];
 #pragma unroll
@@ -211,10 +218,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) kf[sk][ks] = frag(kt, 32 * sk + li, ks);
         wait_lds();                                   // fragments are in registers: the tile's space is free
-        if (has_next) issue_k(kvh + 1);
+        // The next head's K tile is requested behind the second step's rows, so that step does not wait for it
+        // (loads retire in order) and the tile has the whole head's arithmetic to arrive in.
         for (int st = 0; st < n_steps; ++st) {
-            // the step's rows are older than the next K tile only in the head's first step
-            if (st == 0 && has_next) wait_loads<kNK>(); else wait_loads<0>();
+            // outstanding here: this step's rows and, in the second step only, the next K tile behind them
+            if (st == 1 && has_next) wait_loads<kNK>(); else wait_loads<0>();
             bf16x8 qf[kKSteps];
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = frag(qt, li, ks);
@@ -223,8 +231,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
             if (kWeighted)      // omega * 2^x = 2^(x + log2 omega); a zero weight gives 2^-inf = 0
                 lse_row -= __builtin_amdgcn_logf(*(const float __attribute__((address_space(3)))*)(uintptr_t)(wt + 4 * li));
             wait_lds();
-            if (st + 1 < n_steps) issue_q(kvh, st + 1);
-            else if (has_next) issue_q(kvh + 1, 0);
+            if (st + 1 < n_steps) {
+                issue_q(kvh, st + 1);
+                if (st == 0 && has_next) issue_k(kvh + kWavesPerBlock);
+            } else if (has_next) {
+                if (n_steps == 1) issue_k(kvh + kWavesPerBlock);
+                issue_q(kvh + kWavesPerBlock, 0);
+            }
 
             const int rb = st % n_row_blocks;
             const int qpos = first_row + 32 * rb + li;              // this lane's window row
@@ -323,7 +336,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         __syncthreads();
         if (threadIdx.x == 0) {
             __threadfence();                          // this workgroup's partial sums are visible before its count is
-            int* cnt = tail.counters + n_seqs + blockIdx.x;
+            int* cnt = tail.counters + n_seqs + b * blocks_per_seq + key_block;
             const int old = atomicAdd(cnt, 1);
             *flag = old == (int)gridDim.y - 1;
             if (*flag) *cnt = 0;                      // back to zero for the next launch
@@ -392,32 +405,40 @@ __global__ __launch_bounds__(256) void fold_stats_kernel(const float2* __restric
 namespace {
 template <int kMode>
 int launch_walk(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev, const pyr_shape& s,
-                int32_t w, int32_t q_window, float scale_log2, const float* row_weights, float* scores, float2* part,
-                hipStream_t stream, const ScoreTail& tail = ScoreTail{nullptr, nullptr, 0, nullptr, nullptr, nullptr},
-                int head_groups = 1) {
+                int32_t min_seqlen, int32_t w, int32_t q_window, float scale_log2, const float* row_weights, float* scores,
+                float2* part, hipStream_t stream,
+                const ScoreTail& tail = ScoreTail{nullptr, nullptr, 0, nullptr, nullptr, nullptr}, int head_groups = 1) {
     const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
-    const int64_t n_blocks = (int64_t)blocks_per_seq * s.n_seqs;
+    DeviceInfo dev;
+    if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
+    // A whole sequence per XCD where that spreads the work evenly by construction (equal lengths, a multiple of the XCD
+    // count); otherwise the plain order, key block after key block over the XCDs: with ragged lengths the sequences
+    // of one XCD can be much longer than another's (measured: 32 sequences of 512...8192 tokens, 0.35 -> 0.51 ms).
+    const int32_t xcds = dev.xccs;
+    const int32_t chunk_blocks = min_seqlen == s.max_seqlen && s.n_seqs % xcds == 0 ? blocks_per_seq : 1;
+    const int64_t chunks = (int64_t)s.n_seqs * ((blocks_per_seq + chunk_blocks - 1) / chunk_blocks);
+    const int64_t n_blocks = (chunks + xcds - 1) / xcds * xcds * chunk_blocks;
     if (n_blocks >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
     dim3 grid((unsigned)n_blocks, (unsigned)head_groups, 1), block(kWavesPerBlock * 64);
     if (s.head_dim == 128)
         hipLaunchKernelGGL((score_kernel<128, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
-                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, q_window, scale_log2,
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, q_window, scale_log2,
                            row_weights, scores, part, tail);
     else
         hipLaunchKernelGGL((score_kernel<64, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
-                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, q_window, scale_log2,
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, q_window, scale_log2,
                            row_weights, scores, part, tail);
     return check_launch();
 }
 }  // namespace
 
 int launch_score(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
-                 const pyr_shape& s, int32_t w, float scale_log2, const float* row_weights, float* scores,
-                 hipStream_t stream) {
+                 const pyr_shape& s, int32_t min_seqlen, int32_t w, float scale_log2, const float* row_weights,
+                 float* scores, hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
-    return row_weights ? launch_walk<kScoresWeighted>(q, k, lse, seq_offsets_dev, s, w, 0, scale_log2, row_weights, scores,
+    return row_weights ? launch_walk<kScoresWeighted>(q, k, lse, seq_offsets_dev, s, min_seqlen, w, 0, scale_log2, row_weights, scores,
                                                       nullptr, stream)
-                       : launch_walk<kScores>(q, k, lse, seq_offsets_dev, s, w, 0, scale_log2, nullptr, scores, nullptr,
+                       : launch_walk<kScores>(q, k, lse, seq_offsets_dev, s, min_seqlen, w, 0, scale_log2, nullptr, scores, nullptr,
                                               stream);
 }
 
@@ -459,14 +480,14 @@ int launch_score_select(const void* q, const void* k, const float* lse, const in
     // fits the tail's LDS and patience
     const bool select = keep_len_dev != nullptr && min_seqlen >= 1 && s.max_seqlen <= kTailSelectMaxLen;
     if (g == 1 && !select)
-        return launch_score(q, k, lse, seq_offsets_dev, s, w, scale_log2, row_weights, scores, stream);
+        return launch_score(q, k, lse, seq_offsets_dev, s, min_seqlen, w, scale_log2, row_weights, scores, stream);
     const size_t counter_bytes = ((size_t)s.n_seqs * (blocks_per_seq + 1) * sizeof(int32_t) + 255) / 256 * 256;
     ScoreTail tail{(int32_t*)tail_ws, (float*)((char*)tail_ws + counter_bytes), s.total_tokens,
                    select ? keep_len_dev : nullptr, kept_idx, out_offsets_dev};
     *selected = select;
-    return row_weights ? launch_walk<kScoresWeighted>(q, k, lse, seq_offsets_dev, s, w, 0, scale_log2, row_weights, scores,
+    return row_weights ? launch_walk<kScoresWeighted>(q, k, lse, seq_offsets_dev, s, min_seqlen, w, 0, scale_log2, row_weights, scores,
                                                       nullptr, stream, tail, g)
-                       : launch_walk<kScores>(q, k, lse, seq_offsets_dev, s, w, 0, scale_log2, nullptr, scores, nullptr,
+                       : launch_walk<kScores>(q, k, lse, seq_offsets_dev, s, min_seqlen, w, 0, scale_log2, nullptr, scores, nullptr,
                                               stream, tail, g);
 }
 
@@ -479,7 +500,7 @@ int launch_window_score(const void* q_win, const void* k, const int32_t* seq_off
                         float scale_log2, const float* row_weights, float* lse_win, void* part, float* scores,
                         hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
-    int rc = launch_walk<kStats>(q_win, k, nullptr, seq_offsets_dev, s, w, 1, scale_log2, nullptr, nullptr, (float2*)part,
+    int rc = launch_walk<kStats>(q_win, k, nullptr, seq_offsets_dev, s, 0, w, 1, scale_log2, nullptr, nullptr, (float2*)part,
                                  stream);
     if (rc != PYR_OK) return rc;
     const int64_t n = (int64_t)s.n_seqs * w * s.n_q_heads;
@@ -487,9 +508,9 @@ int launch_window_score(const void* q_win, const void* k, const int32_t* seq_off
     hipLaunchKernelGGL(fold_stats_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const float2*)part,
                        seq_offsets_dev, s.n_seqs, s.n_q_heads, w, lse_win);
     if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
-    return row_weights ? launch_walk<kScoresWeighted>(q_win, k, lse_win, seq_offsets_dev, s, w, 1, scale_log2, row_weights,
+    return row_weights ? launch_walk<kScoresWeighted>(q_win, k, lse_win, seq_offsets_dev, s, 0, w, 1, scale_log2, row_weights,
                                                       scores, nullptr, stream)
-                       : launch_walk<kScores>(q_win, k, lse_win, seq_offsets_dev, s, w, 1, scale_log2, nullptr, scores,
+                       : launch_walk<kScores>(q_win, k, lse_win, seq_offsets_dev, s, 0, w, 1, scale_log2, nullptr, scores,
                                               nullptr, stream);
 }
 

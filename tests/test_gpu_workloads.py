@@ -240,3 +240,19 @@ def test_cfg3_pyramid_chain(chain, last_layer):
         assert np.array_equal(chain.pos_dev.cpu().numpy(), chain.origin % chain.base.seq_lens[0])
         print(f"[cfg3 chain] worst out max {chain.worst[0]:.2e} mean {chain.worst[1]:.2e}, "
               f"score rel {chain.worst[2]:.2e}, swapped in band {chain.swapped}", flush=True)
+
+
+@pytest.mark.gpu
+def test_diagnostic_launches_complete():
+    """The two ceilings bench.py reports (MFMA only, read only) run to completion and leave their sinks alone."""
+    import torch
+    from paper_2405_12532_amd import binding as pyr
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flops = pyr.diag_mfma_only(10, sink)
+    assert flops > 0
+    data = torch.ones(4 << 20, dtype=torch.uint8, device="cuda")
+    isink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for k_layout in (0, 1):
+        pyr.diag_read_stream(data, data.numel(), k_layout, isink)
+    torch.cuda.synchronize()
+    assert float(sink.item()) == 0.0 and int(isink.item()) == 0

@@ -137,6 +137,17 @@ def test_compact_and_select_reject_bad_arguments():
     assert lib.pyr_select(None, 0x2000, off.data_ptr(), 0x3000, keep.data_ptr(), 2, 2, 0x4000, 0x5000, None) == -1
 
 
+def test_diagnostics_reject_bad_arguments_before_launching():
+    lib = binding.load()
+    fl = ctypes.c_double(0.0)
+    assert lib.pyr_diag_mfma_only(10, None, None, ctypes.byref(fl)) == -1
+    assert lib.pyr_diag_mfma_only(0, 0x1000, None, ctypes.byref(fl)) == -2
+    assert lib.pyr_diag_read_stream(None, 1 << 19, 0, 0x2000, None) == -1
+    assert lib.pyr_diag_read_stream(0x1000, 1 << 19, 0, None, None) == -1
+    assert lib.pyr_diag_read_stream(0x1000, 0, 0, 0x2000, None) == -2
+    assert lib.pyr_diag_read_stream(0x1000, (1 << 19) + 16, 1, 0x2000, None) == -2      # not whole workgroups
+
+
 def test_position_and_weight_entry_points_reject_bad_arguments():
     lib = binding.load()
     assert lib.pyr_gather_positions(0x1000, 0x2000, -1, 0x3000, None) == -2

@@ -94,7 +94,7 @@ template <int D, int kMode>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
     const int32_t* __restrict__ seq_offsets, int32_t n_seqs, int32_t n_q_heads, int32_t n_kv_heads, int32_t w,
-    int32_t blocks_per_seq, int32_t chunk_blocks, int32_t xcds, int32_t q_window, float c,
+    int32_t blocks_per_seq, int32_t chunk_blocks, int32_t xcds, int32_t head_step, int32_t q_window, float c,
     const float* __restrict__ row_weights, float* __restrict__ scores, float2* __restrict__ part, ScoreTail tail) {
     constexpr bool kWeighted = kMode == kScoresWeighted;
     constexpr int kKSteps = D / 16;
@@ -134,7 +134,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     // this workgroup's share of the KV heads (all of them unless the launcher split them over gridDim.y), halved
     // between the two wavefronts
     const int wg_heads = n_kv_heads / (int)gridDim.y, wg_first = (int)blockIdx.y * wg_heads;
-    const int kvh_begin = wg_first + wave, kvh_end = wg_first + wg_heads;     // interleaved: the wavefronts read adjacent heads at the same time
+    // The two wavefronts take alternate heads (so they read adjacent heads at the same time), and, where the launcher
+    // asks for it (head_step != 0), every key block starts its walk at another head: workgroups that run side by side
+    // then read different 256-byte columns of their token rows, which spreads them over the memory channels when the
+    // rows are a power of two apart (a read-only stream over 8 KB rows: 5.5 -> 5.9 TB/s with steps of 7; 1 and 8 are
+    // worse than none).
+    const int head_rot = (key_block * head_step) % wg_heads;
+    auto head_at = [&](int i) { const int r = i + head_rot; return wg_first + (r >= wg_heads ? r - wg_heads : r); };   // i < wg_heads
 
     float acc[2][16];
 #pragma unroll
@@ -204,13 +210,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a;
     };
 
-    if (kvh_begin < kvh_end) {
-        issue_k(kvh_begin);
-        issue_q(kvh_begin, 0);
+    if (wave < wg_heads) {
+        issue_k(head_at(wave));
+        issue_q(head_at(wave), 0);
     }
     // Outstanding loads at the top of a head: its K tile (oldest), then its first step's rows.
-    for (int kvh = kvh_begin; kvh < kvh_end; kvh += kWavesPerBlock) {
-        const bool has_next = kvh + kWavesPerBlock < kvh_end;
+    for (int hi = wave; hi < wg_heads; hi += kWavesPerBlock) {
+        const bool has_next = hi + kWavesPerBlock < wg_heads;
+        const int kvh = head_at(hi), kvh_next = has_next ? head_at(hi + kWavesPerBlock) : kvh;
         wait_loads<kStepLoads>();                     // the K tile has landed
         bf16x8 kf[2][kKSteps];
 #pragma unroll
@@ -233,10 +240,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
             wait_lds();
             if (st + 1 < n_steps) {
                 issue_q(kvh, st + 1);
-                if (st == 0 && has_next) issue_k(kvh + kWavesPerBlock);
+                if (st == 0 && has_next) issue_k(kvh_next);
             } else if (has_next) {
-                if (n_steps == 1) issue_k(kvh + kWavesPerBlock);
-                issue_q(kvh + kWavesPerBlock, 0);
+                if (n_steps == 1) issue_k(kvh_next);
+                issue_q(kvh_next, 0);
             }
 
             const int rb = st % n_row_blocks;
@@ -416,17 +423,21 @@ int launch_walk(const void* q, const void* k, const float* lse, const int32_t* s
     // of one XCD can be much longer than another's (measured: 32 sequences of 512...8192 tokens, 0.35 -> 0.51 ms).
     const int32_t xcds = dev.xccs;
     const int32_t chunk_blocks = min_seqlen == s.max_seqlen && s.n_seqs % xcds == 0 ? blocks_per_seq : 1;
+    // (rows of 10 KB - 40 heads - are spread well as they are, and lose 4 % to the rotation: neighbouring key blocks then
+    //  no longer share the window's Q rows of one head in L2)
+    const size_t k_row_bytes = (size_t)s.n_kv_heads * s.head_dim * 2;
+    const int32_t head_step = (k_row_bytes & (k_row_bytes - 1)) == 0 ? 7 : 0;
     const int64_t chunks = (int64_t)s.n_seqs * ((blocks_per_seq + chunk_blocks - 1) / chunk_blocks);
     const int64_t n_blocks = (chunks + xcds - 1) / xcds * xcds * chunk_blocks;
     if (n_blocks >= (int64_t)1 << 31) return PYR_ERR_UNSUPPORTED;
     dim3 grid((unsigned)n_blocks, (unsigned)head_groups, 1), block(kWavesPerBlock * 64);
     if (s.head_dim == 128)
         hipLaunchKernelGGL((score_kernel<128, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
-                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, q_window, scale_log2,
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, head_step, q_window, scale_log2,
                            row_weights, scores, part, tail);
     else
         hipLaunchKernelGGL((score_kernel<64, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
-                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, q_window, scale_log2,
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, head_step, q_window, scale_log2,
                            row_weights, scores, part, tail);
     return check_launch();
 }

@@ -134,11 +134,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     // this workgroup's share of the KV heads (all of them unless the launcher split them over gridDim.y), halved
     // between the two wavefronts
     const int wg_heads = n_kv_heads / (int)gridDim.y, wg_first = (int)blockIdx.y * wg_heads;
-    // The two wavefronts take alternate heads (so they read adjacent heads at the same time), and, where the launcher
-    // asks for it (head_step != 0), every key block starts its walk at another head: workgroups that run side by side
-    // then read different 256-byte columns of their token rows, which spreads them over the memory channels when the
-    // rows are a power of two apart (a read-only stream over 8 KB rows: 5.5 -> 5.9 TB/s with steps of 7; 1 and 8 are
-    // worse than none).
+    // Each wavefront takes half of the workgroup's heads, and, where the launcher asks for it (head_step != 0), every
+    // key block starts its walk at another head: workgroups that run side by side then read different 256-byte
+    // columns of their token rows, which spreads them over the memory channels when the rows are a power of two
+    // apart (a read-only stream over 8 KB rows: 5.5 -> 5.9 TB/s with steps of 7; 1 and 8 are worse than none).
     const int head_rot = (key_block * head_step) % wg_heads;
     auto head_at = [&](int i) { const int r = i + head_rot; return wg_first + (r >= wg_heads ? r - wg_heads : r); };   // i < wg_heads
 
@@ -210,14 +209,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         return *(const bf16x8 __attribute__((address_space(3)))*)(uintptr_t)a;
     };
 
-    if (wave < wg_heads) {
-        issue_k(head_at(wave));
-        issue_q(head_at(wave), 0);
+    const int hi_begin = wave * wg_heads / kWavesPerBlock, hi_end = (wave + 1) * wg_heads / kWavesPerBlock;
+    if (hi_begin < hi_end) {
+        issue_k(head_at(hi_begin));
+        issue_q(head_at(hi_begin), 0);
     }
     // Outstanding loads at the top of a head: its K tile (oldest), then its first step's rows.
-    for (int hi = wave; hi < wg_heads; hi += kWavesPerBlock) {
-        const bool has_next = hi + kWavesPerBlock < wg_heads;
-        const int kvh = head_at(hi), kvh_next = has_next ? head_at(hi + kWavesPerBlock) : kvh;
+    for (int hi = hi_begin; hi < hi_end; ++hi) {
+        const bool has_next = hi + 1 < hi_end;
+        const int kvh = head_at(hi), kvh_next = has_next ? head_at(hi + 1) : kvh;
         wait_loads<kStepLoads>();                     // the K tile has landed
         bf16x8 kf[2][kKSteps];
 #pragma unroll
@@ -225,11 +225,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) kf[sk][ks] = frag(kt, 32 * sk + li, ks);
         wait_lds();                                   // fragments are in registers: the tile's space is free
-        // The next head's K tile is requested behind the second step's rows, so that step does not wait for it
-        // (loads retire in order) and the tile has the whole head's arithmetic to arrive in.
+        if (has_next) issue_k(kvh_next);
         for (int st = 0; st < n_steps; ++st) {
-            // outstanding here: this step's rows and, in the second step only, the next K tile behind them
-            if (st == 1 && has_next) wait_loads<kNK>(); else wait_loads<0>();
+            // the step's rows are older than the next K tile only in the head's first step
+            if (st == 0 && has_next) wait_loads<kNK>(); else wait_loads<0>();
             bf16x8 qf[kKSteps];
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) qf[ks] = frag(qt, li, ks);
@@ -238,13 +237,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
             if (kWeighted)      // omega * 2^x = 2^(x + log2 omega); a zero weight gives 2^-inf = 0
                 lse_row -= __builtin_amdgcn_logf(*(const float __attribute__((address_space(3)))*)(uintptr_t)(wt + 4 * li));
             wait_lds();
-            if (st + 1 < n_steps) {
-                issue_q(kvh, st + 1);
-                if (st == 0 && has_next) issue_k(kvh_next);
-            } else if (has_next) {
-                if (n_steps == 1) issue_k(kvh_next);
-                issue_q(kvh_next, 0);
-            }
+            if (st + 1 < n_steps) issue_q(kvh, st + 1);
+            else if (has_next) issue_q(kvh_next, 0);
 
             const int rb = st % n_row_blocks;
             const int qpos = first_row + 32 * rb + li;              // this lane's window row
@@ -433,12 +427,12 @@ int launch_walk(const void* q, const void* k, const float* lse, const int32_t* s
     dim3 grid((unsigned)n_blocks, (unsigned)head_groups, 1), block(kWavesPerBlock * 64);
     if (s.head_dim == 128)
         hipLaunchKernelGGL((score_kernel<128, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
-                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, head_step, q_window, scale_log2,
-                           row_weights, scores, part, tail);
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, head_step,
+                           q_window, scale_log2, row_weights, scores, part, tail);
     else
         hipLaunchKernelGGL((score_kernel<64, kMode>), grid, block, 0, stream, (const uint16_t*)q, (const uint16_t*)k, lse,
-                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, head_step, q_window, scale_log2,
-                           row_weights, scores, part, tail);
+                           seq_offsets_dev, s.n_seqs, s.n_q_heads, s.n_kv_heads, w, blocks_per_seq, chunk_blocks, xcds, head_step,
+                           q_window, scale_log2, row_weights, scores, part, tail);
     return check_launch();
 }
 }  // namespace

@@ -401,7 +401,7 @@ int pyr_decode_update(const void* q_win, const void* k, const void* v,
     hipStream_t st = (hipStream_t)stream;
     pyr_shape s = *shape;
     s.max_seqlen = info.max_len;
-    rc = pyr::launch_window_score(q_win, k, seq_offsets_dev, s, w, scale_log2(softmax_scale, shape->head_dim),
+    rc = pyr::launch_window_score(q_win, k, seq_offsets_dev, s, info.min_len, w, scale_log2(softmax_scale, shape->head_dim),
                                   row_weights_dev, lse_win, part, scores, st);
     if (rc != PYR_OK) return rc;
     rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,

@@ -57,7 +57,7 @@ int launch_score_select(const void* q, const void* k, const float* lse, const in
 // [B, w, Hq], then the score pass.  part holds window_score_part_bytes() bytes.
 size_t window_score_part_bytes(const pyr_shape& shape, int32_t w);
 int launch_window_score(const void* q_win, const void* k, const int32_t* seq_offsets_dev, const pyr_shape& shape,
-                        int32_t w, float scale_log2, const float* row_weights, float* lse_win, void* part,
+                        int32_t min_seqlen, int32_t w, float scale_log2, const float* row_weights, float* lse_win, void* part,
                         float* scores, hipStream_t stream);
 
 int launch_gather_positions(const int32_t* pos, const int32_t* kept_idx, int64_t n_kept, int32_t* pos_out,

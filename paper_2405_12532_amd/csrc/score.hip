@@ -501,11 +501,11 @@ size_t window_score_part_bytes(const pyr_shape& s, int32_t w) {
     return blocks_per_seq * (size_t)s.n_seqs * (size_t)w * (size_t)s.n_q_heads * sizeof(float2);
 }
 
-int launch_window_score(const void* q_win, const void* k, const int32_t* seq_offsets_dev, const pyr_shape& s, int32_t w,
-                        float scale_log2, const float* row_weights, float* lse_win, void* part, float* scores,
+int launch_window_score(const void* q_win, const void* k, const int32_t* seq_offsets_dev, const pyr_shape& s,
+                        int32_t min_seqlen, int32_t w, float scale_log2, const float* row_weights, float* lse_win, void* part, float* scores,
                         hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
-    int rc = launch_walk<kStats>(q_win, k, nullptr, seq_offsets_dev, s, 0, w, 1, scale_log2, nullptr, nullptr, (float2*)part,
+    int rc = launch_walk<kStats>(q_win, k, nullptr, seq_offsets_dev, s, min_seqlen, w, 1, scale_log2, nullptr, nullptr, (float2*)part,
                                  stream);
     if (rc != PYR_OK) return rc;
     const int64_t n = (int64_t)s.n_seqs * w * s.n_q_heads;
@@ -513,9 +513,9 @@ int launch_window_score(const void* q_win, const void* k, const int32_t* seq_off
     hipLaunchKernelGGL(fold_stats_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const float2*)part,
                        seq_offsets_dev, s.n_seqs, s.n_q_heads, w, lse_win);
     if (check_launch() != PYR_OK) return PYR_ERR_LAUNCH;
-    return row_weights ? launch_walk<kScoresWeighted>(q_win, k, lse_win, seq_offsets_dev, s, 0, w, 1, scale_log2, row_weights,
+    return row_weights ? launch_walk<kScoresWeighted>(q_win, k, lse_win, seq_offsets_dev, s, min_seqlen, w, 1, scale_log2, row_weights,
                                                       scores, nullptr, stream)
-                       : launch_walk<kScores>(q_win, k, lse_win, seq_offsets_dev, s, 0, w, 1, scale_log2, nullptr, scores,
+                       : launch_walk<kScores>(q_win, k, lse_win, seq_offsets_dev, s, min_seqlen, w, 1, scale_log2, nullptr, scores,
                                               nullptr, stream);
 }
 

@@ -55,6 +55,9 @@ def separate_calls(lib, x, wl, pos):
     ((300, 0, 120), 4, 4, 64, 16),            # an empty sequence: selection launched separately
     ((900,) * 40, 8, 8, 128, 64),             # enough key blocks for the chip: one head group, selection in the tail
     ((2048,) * 20, 8, 8, 128, 64),            # ... and selection launched separately
+    ((300,) * 8, 8, 8, 64, 32),               # equal lengths, eight sequences: a sequence per XCD, 2 head groups, tail selection
+    ((130,) * 16, 4, 2, 128, 64),             # ... GQA 2, three key blocks each, the last one ragged
+    ((1100,) * 24, 16, 16, 64, 64),           # ... one head group, selection launched separately
 ])
 def test_fused_step_equals_the_separate_calls(lib, lens, Hq, Hkv, d, w):
     wl = synth.shrunk(synth.workload("cfg2"), lens, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, w=w, hidden_dim=256)

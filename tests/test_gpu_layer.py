@@ -81,6 +81,18 @@ def test_many_short_sequences(lib):
     run_and_check(lib, wl, hidden=False)
 
 
+@pytest.mark.parametrize("lens,Hq,Hkv,d,w", [
+    ((300,) * 8, 8, 8, 64, 32),                 # 2 head groups, selection in the score pass's tail
+    ((130,) * 16, 4, 2, 128, 64),               # GQA 2, the last key block ragged
+    ((1100,) * 8, 8, 4, 64, 64),                # beyond the tail's reach: the selection kernel
+])
+def test_equal_lengths_in_multiples_of_eight(lib, lens, Hq, Hkv, d, w):
+    """Batches of equal lengths and a multiple of eight sequences: the score pass keeps a sequence's key blocks on
+    one XCD (another workgroup-to-block map than any ragged batch gets) and rotates the walk over the heads."""
+    wl = synth.shrunk(synth.workload("cfg2"), lens, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, w=w, hidden_dim=128)
+    run_and_check(lib, wl)
+
+
 def test_custom_softmax_scale(lib):
     wl = synth.shrunk(synth.workload("cfg2"), (333, 100), n_q_heads=4, n_kv_heads=4, head_dim=64, w=20)
     run_and_check(lib, wl, scale=0.2)

@@ -148,7 +148,7 @@ class Step:
         mark(5)
 
     def fused(self):
-        """the same step through pyr_prefill_layer_fused: three launches"""
+        """the same step through pyr_prefill_layer_fused: four launches"""
         self.pyr.prefill_layer_fused(self.q, self.k, self.v, self.off_d, self.off_h, self.shape, self.wl.w, 0.0, self.keep_d,
                                      self.keep_h, None, self.hidden, self.D * 2, None, self.out, self.scores, self.kept,
                                      self.out_off, self.k_out, self.v_out, self.hidden_out, None, self.ws, self.ws_bytes)

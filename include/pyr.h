@@ -250,11 +250,9 @@ PYR_API int pyr_prefill_layer_ex(const void* q, const void* k, const void* v,
 /*
  * The whole layer step in as few launches as it takes (Appendix A.1 and the Limitations section: at small
  * batch the cost of selecting the PvC eats the gain - there every launch counts): attention; the score pass,
- * in which the workgroup that completes a sequence's scores selects its PvC at once (sequences of up to 1024
- * tokens, none empty; otherwise the selection is a launch of its own: with 128 lanes it takes longer than
- * the launch costs) and, when the batch is too small to
- * fill the chip with one workgroup per 64 keys, the KV heads are split over several workgroups whose partial
- * sums the last of them adds in a fixed order; ONE gather for K, V, the hidden rows and the position ids.
+ * in which, when the batch is too small to fill the chip with one workgroup per 64 keys, the KV heads are
+ * split over several workgroups whose partial sums the last of them adds in a fixed order; the selection;
+ * ONE gather for K, V, the hidden rows and the position ids.
  * pyr_prefill_layer and pyr_prefill_layer_ex are this call without the hidden rows.
  *   hidden             dev, rows of hidden_row_bytes bytes (a multiple of 16) indexed by packed row; hidden_out
  *                      dev [sum k_b rows], written; both NULL skips them

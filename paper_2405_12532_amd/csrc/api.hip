@@ -309,20 +309,15 @@ int pyr_prefill_layer_fused(const void* q, const void* k, const void* v,
     pyr_shape s = *shape;
     s.max_seqlen = info.max_len;
 
-    // three launches (four for a ragged batch: the tile map): attention, which also clears the counters of the
-    // next one; the score pass, whose last workgroup per sequence selects; one gather for everything
+    // four launches (five for a ragged batch: the tile map): attention, which also clears the counters of the
+    // next one; the score pass; the selection; one gather for everything
     rc = pyr::launch_attention(q, k, v, seq_offsets_dev, seq_offsets_host, s, info.uniform_len, c, out, lse, tile_map,
                                (int32_t*)tail_ws, pyr::score_tail_counters(s), st);
     if (rc != PYR_OK) return rc;
-    bool selected = false;
-    rc = pyr::launch_score_select(q, k, lse, seq_offsets_dev, s, info.min_len, w, c, row_weights_dev, scores, keep_len_dev,
-                                  kept_idx, out_offsets_dev, tail_ws, &selected, st);
+    rc = pyr::launch_score_groups(q, k, lse, seq_offsets_dev, s, info.min_len, w, c, row_weights_dev, scores, tail_ws, st);
     if (rc != PYR_OK) return rc;
-    if (!selected) {
-        rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx,
-                                out_offsets_dev, st);
-        if (rc != PYR_OK) return rc;
-    }
+    rc = pyr::launch_select(scores, seq_offsets_dev, keep_len_dev, s.n_seqs, info.max_len, w, kept_idx, out_offsets_dev, st);
+    if (rc != PYR_OK) return rc;
     if (total_kept > 0) {
         const void* srcs[3];
         void* dsts[3];

@@ -41,16 +41,14 @@ int launch_score(const void* q, const void* k, const float* lse, const int32_t* 
                  const pyr_shape& shape, int32_t min_seqlen, int32_t w, float scale_log2, const float* row_weights,
                  float* scores, hipStream_t stream);
 
-// The score pass with its small-batch extras (see score.hip): KV heads split over several workgroups per key block
-// when the grid is small, and the top-k selection run by the workgroup that completes a sequence (*selected tells
-// whether it was; if not, launch_select is still to be called).  tail_ws: score_tail_bytes() bytes whose first
-// score_tail_counters() int32 are zero at launch (the kernel leaves them zero).
+// The score pass with its small-batch extra (see score.hip): the KV heads split over several workgroups per key
+// block when the grid is small.  tail_ws: score_tail_bytes() bytes whose first score_tail_counters() int32 are zero
+// at launch (the kernel leaves them zero).
 size_t score_tail_bytes(const pyr_shape& shape);
 int32_t score_tail_counters(const pyr_shape& shape);
-int launch_score_select(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
+int launch_score_groups(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
                         const pyr_shape& shape, int32_t min_seqlen, int32_t w, float scale_log2,
-                        const float* row_weights, float* scores, const int32_t* keep_len_dev, int32_t* kept_idx,
-                        int32_t* out_offsets_dev, void* tail_ws, bool* selected, hipStream_t stream);
+                        const float* row_weights, float* scores, void* tail_ws, hipStream_t stream);
 
 // Generation phase: the same scores from the window's own query buffer q_win [B, w, Hq, d]
 // (right-aligned), three launches: per-block row statistics -> part, folded into lse_win

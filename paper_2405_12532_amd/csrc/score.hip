@@ -37,10 +37,12 @@
 // selection overhead eats the gain at small batch).  The launcher may therefore split the KV heads over
 // gridDim.y workgroups per key block; each writes its partial sums, and the workgroup that arrives last at
 // the block's counter adds them up in head-group order (so the result does not depend on who was last).
-// In the same way the workgroup that completes the last key block of a SEQUENCE runs the top-k selection
-// for it at once (select_device.h), which saves the selection's own launch.  The counters live in the
-// caller's workspace, start at zero and are put back to zero by their last arrival.
-#include "select_device.h"
+// (Letting the workgroup that completes a sequence's scores run the top-k selection as well was built and
+// measured: it replaces a launch that costs as much as the selection it carries, and was slower at every
+// shape - 27.8 against 26.5 us per step at one 256-token prompt, 40.0 against 39.5 ms over the 32-layer
+// pyramid at batch 64 - so the selection stays a kernel of its own.)  The counters live in the caller's
+// workspace, start at zero and are put back to zero by their last arrival.
+#include "pyr_internal.h"
 
 namespace pyr {
 namespace {
@@ -51,18 +53,14 @@ constexpr int kKeysPerBlock = 64;
 
 typedef __attribute__((address_space(3))) char* lptr_t;
 
-constexpr int kTailSelectMaxLen = 1024;      // longest sequence the score pass's tail selects for: its 128 lanes take about three times as long as the
-                                             // selection kernel's 1024 (measured at 2048 keys: 28 us against 10), so beyond this the launch is cheaper
 constexpr int kMaxHeadGroups = 16;
 
-// What the last-arriving workgroups of the score pass do (all pointers device; counters == nullptr: nothing).
+// What the last-arriving workgroup of a key block does when the KV heads are split over gridDim.y workgroups
+// (all pointers device; counters == nullptr: no split).
 struct ScoreTail {
-    int32_t* counters;            // [n_seqs] per sequence, then [gridDim.x] per key block; zero at launch
-    float* part_sums;             // [gridDim.y, total_tokens] partial scores when the KV heads are split over gridDim.y
+    int32_t* counters;            // [n_seqs * blocks_per_seq] one per key block; zero at launch
+    float* part_sums;             // [gridDim.y, total_tokens] partial scores
     int32_t total_tokens;
-    const int32_t* keep_len;      // nullptr: no selection in the tail
-    int32_t* kept_idx;
-    int32_t* out_offsets;
 };
 
 // 64 lanes x 16 bytes (or x 4 bytes) from base + voff[lane] to LDS at lds_addr + 16 (4) * lane.
@@ -107,7 +105,6 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
     constexpr int kRedBytes = kWavesPerBlock * 2 * 64 * 17 * 4;     // +1 column: conflict-free column sums
     constexpr int kSmemBytes = kWavesPerBlock * (kKBytes + kQBytes + 2 * kLseBytes);
     static_assert(kSmemBytes >= kRedBytes, "the final reduction reuses the tiles' space");
-    static_assert(kSmemBytes >= (int)sizeof(SelectShared) + 4 * kTailSelectMaxLen, "the selection in the tail reuses it too");
     __shared__ __align__(1024) char smem[kSmemBytes];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -329,45 +326,28 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void score_kernel(
         float* dst = gridDim.y > 1 ? tail.part_sums + (size_t)blockIdx.y * tail.total_tokens : scores;
         if (key < S) dst[row0 + key] = sum * norm;
     }
-    if (tail.counters == nullptr) return;
+    if (gridDim.y == 1) return;
 
-    // ---- what the last arrivals do.  (Uniform over the workgroup from here on.)
+    // ---- the last of this key block's head groups to arrive adds up the partial sums, in head-group order.
+    // (Uniform over the workgroup from here on.)
     int* flag = (int*)smem;                           // (past the reduction's reads: behind a barrier)
-    if (gridDim.y > 1) {
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            __threadfence();                          // this workgroup's partial sums are visible before its count is
-            int* cnt = tail.counters + n_seqs + b * blocks_per_seq + key_block;
-            const int old = atomicAdd(cnt, 1);
-            *flag = old == (int)gridDim.y - 1;
-            if (*flag) *cnt = 0;                      // back to zero for the next launch
-        }
-        __syncthreads();
-        if (*flag == 0) return;
-        __threadfence();                              // the other head groups' partial sums are visible now
-        const int key = key_base + (int)threadIdx.x;
-        if (threadIdx.x < 64 && key < S) {
-            float sum = 0.f;
-            for (int hg = 0; hg < (int)gridDim.y; ++hg) sum += tail.part_sums[(size_t)hg * tail.total_tokens + row0 + key];
-            scores[row0 + key] = sum;
-        }
-    }
-    if (tail.keep_len == nullptr) return;
     __syncthreads();
     if (threadIdx.x == 0) {
-        __threadfence();
-        int* cnt = tail.counters + b;
+        __threadfence();                              // this workgroup's partial sums are visible before its count is
+        int* cnt = tail.counters + b * blocks_per_seq + key_block;
         const int old = atomicAdd(cnt, 1);
-        *flag = old == (S + kKeysPerBlock - 1) / kKeysPerBlock - 1;
-        if (*flag) *cnt = 0;
+        *flag = old == (int)gridDim.y - 1;
+        if (*flag) *cnt = 0;                          // back to zero for the next launch
     }
     __syncthreads();
     if (*flag == 0) return;
-    __threadfence();                                  // every key block's scores of this sequence are visible now
-    __syncthreads();                                  // (flag has been read by everybody: its space is reused)
-    select_sequence<kWavesPerBlock * 64>(b, scores, seq_offsets, tail.keep_len, w, (uint32_t*)(smem + sizeof(SelectShared)),
-                                         (kSmemBytes - (int)sizeof(SelectShared)) / 4, (SelectShared*)smem, tail.kept_idx,
-                                         tail.out_offsets);
+    __threadfence();                                  // the other head groups' partial sums are visible now
+    const int key = key_base + (int)threadIdx.x;
+    if (threadIdx.x < 64 && key < S) {
+        float sum = 0.f;
+        for (int hg = 0; hg < (int)gridDim.y; ++hg) sum += tail.part_sums[(size_t)hg * tail.total_tokens + row0 + key];
+        scores[row0 + key] = sum;
+    }
 }
 
 // Row denominators of the window rows from the per-block statistics: for every (sequence,
@@ -408,7 +388,7 @@ template <int kMode>
 int launch_walk(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev, const pyr_shape& s,
                 int32_t min_seqlen, int32_t w, int32_t q_window, float scale_log2, const float* row_weights, float* scores,
                 float2* part, hipStream_t stream,
-                const ScoreTail& tail = ScoreTail{nullptr, nullptr, 0, nullptr, nullptr, nullptr}, int head_groups = 1) {
+                const ScoreTail& tail = ScoreTail{nullptr, nullptr, 0}, int head_groups = 1) {
     const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
     DeviceInfo dev;
     if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
@@ -459,7 +439,7 @@ static int pick_head_groups(int64_t n_blocks, int n_kv_heads, int compute_units)
 
 size_t score_tail_bytes(const pyr_shape& s) {
     const size_t blocks_per_seq = ((size_t)s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
-    const size_t counters = ((size_t)s.n_seqs * (blocks_per_seq + 1) * sizeof(int32_t) + 255) / 256 * 256;
+    const size_t counters = ((size_t)s.n_seqs * blocks_per_seq * sizeof(int32_t) + 255) / 256 * 256;
     // partial sums are only ever used by grids of fewer than 2 x 256 key blocks
     const size_t parts = (size_t)s.n_seqs * blocks_per_seq < 1024 ? (size_t)kMaxHeadGroups * s.total_tokens * sizeof(float) : 0;
     return counters + (parts + 255) / 256 * 256;
@@ -467,29 +447,21 @@ size_t score_tail_bytes(const pyr_shape& s) {
 
 int32_t score_tail_counters(const pyr_shape& s) {
     const int32_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
-    return s.n_seqs * (blocks_per_seq + 1);
+    return s.n_seqs * blocks_per_seq;
 }
 
-int launch_score_select(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
+int launch_score_groups(const void* q, const void* k, const float* lse, const int32_t* seq_offsets_dev,
                         const pyr_shape& s, int32_t min_seqlen, int32_t w, float scale_log2, const float* row_weights,
-                        float* scores, const int32_t* keep_len_dev, int32_t* kept_idx, int32_t* out_offsets_dev,
-                        void* tail_ws, bool* selected, hipStream_t stream) {
-    *selected = false;
+                        float* scores, void* tail_ws, hipStream_t stream) {
     if (s.n_seqs == 0 || s.max_seqlen == 0) return PYR_OK;
     DeviceInfo dev;
     if (device_info(&dev) != PYR_OK) return PYR_ERR_LAUNCH;
     const int64_t blocks_per_seq = (s.max_seqlen + kKeysPerBlock - 1) / kKeysPerBlock;
     const int64_t n_blocks = blocks_per_seq * s.n_seqs;
     const int g = n_blocks < 1024 ? pick_head_groups(n_blocks, s.n_kv_heads, dev.compute_units) : 1;
-    // the tail selects when every sequence has a workgroup that can be its last (no empty sequence) and the longest
-    // fits the tail's LDS and patience
-    const bool select = keep_len_dev != nullptr && min_seqlen >= 1 && s.max_seqlen <= kTailSelectMaxLen;
-    if (g == 1 && !select)
-        return launch_score(q, k, lse, seq_offsets_dev, s, min_seqlen, w, scale_log2, row_weights, scores, stream);
-    const size_t counter_bytes = ((size_t)s.n_seqs * (blocks_per_seq + 1) * sizeof(int32_t) + 255) / 256 * 256;
-    ScoreTail tail{(int32_t*)tail_ws, (float*)((char*)tail_ws + counter_bytes), s.total_tokens,
-                   select ? keep_len_dev : nullptr, kept_idx, out_offsets_dev};
-    *selected = select;
+    if (g == 1) return launch_score(q, k, lse, seq_offsets_dev, s, min_seqlen, w, scale_log2, row_weights, scores, stream);
+    const size_t counter_bytes = ((size_t)s.n_seqs * blocks_per_seq * sizeof(int32_t) + 255) / 256 * 256;
+    ScoreTail tail{(int32_t*)tail_ws, (float*)((char*)tail_ws + counter_bytes), s.total_tokens};
     return row_weights ? launch_walk<kScoresWeighted>(q, k, lse, seq_offsets_dev, s, min_seqlen, w, 0, scale_log2, row_weights, scores,
                                                       nullptr, stream, tail, g)
                        : launch_walk<kScores>(q, k, lse, seq_offsets_dev, s, min_seqlen, w, 0, scale_log2, nullptr, scores, nullptr,

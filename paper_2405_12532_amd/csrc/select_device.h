@@ -1,7 +1,6 @@
 // Device code of the segmented top-k (Algorithm 1, TopP(A_e, p) with the retention ratio turned
-// into a count, followed by the recent window that is always kept), shared by the stand-alone
-// selection kernel (one workgroup of 1024 lanes per sequence) and by the tail of the score pass
-// (the workgroup that completes a sequence's scores selects for it, 128 lanes).
+// into a count, followed by the recent window that is always kept), written for a workgroup of
+// any multiple of 64 lanes; the selection kernel (select.hip) runs it with 1024 lanes per sequence.
 //
 // The paper names the sort inside TopP as the one extra cost of the method that matters
 // (Appendix A.1).  Nothing is sorted here: the workgroup finds the value of the need-th largest

@@ -1,5 +1,5 @@
-"""The merged layer step (pyr_prefill_layer_fused: attention, score pass with the selection in its tail and the
-KV heads split over workgroups at small batch, one gather for K, V, hidden rows and position ids) against the
+"""The merged layer step (pyr_prefill_layer_fused: attention, score pass with the KV heads split over workgroups
+at small batch, selection, one gather for K, V, hidden rows and position ids) against the
 oracle and against the same step through the separate entry points."""
 import numpy as np
 import pytest
@@ -47,17 +47,17 @@ def separate_calls(lib, x, wl, pos):
 
 
 @pytest.mark.parametrize("lens,Hq,Hkv,d,w", [
-    ((2048,), 32, 32, 128, 64),               # one prompt at the 7B head shape: 16 head groups, selection launched separately
-    ((1000,), 32, 32, 128, 64),               # ... short enough for the selection in the tail
-    ((700, 33, 1000), 16, 8, 128, 64),        # ragged, GQA 2: 4 head groups, selection in the tail
+    ((2048,), 32, 32, 128, 64),               # one prompt at the 7B head shape: 16 head groups
+    ((1000,), 32, 32, 128, 64),               # ... a shorter one, its last key block ragged
+    ((700, 33, 1000), 16, 8, 128, 64),        # ragged, GQA 2: 4 head groups
     ((256,), 8, 8, 64, 16),                   # the smallest workload's shape: 4 head groups
-    ((5000, 300), 8, 4, 64, 32),              # a sequence beyond the tail's reach: selection launched separately
-    ((300, 0, 120), 4, 4, 64, 16),            # an empty sequence: selection launched separately
-    ((900,) * 40, 8, 8, 128, 64),             # enough key blocks for the chip: one head group, selection in the tail
-    ((2048,) * 20, 8, 8, 128, 64),            # ... and selection launched separately
-    ((300,) * 8, 8, 8, 64, 32),               # equal lengths, eight sequences: a sequence per XCD, 2 head groups, tail selection
+    ((5000, 300), 8, 4, 64, 32),              # a long and a short sequence, 2 head groups
+    ((300, 0, 120), 4, 4, 64, 16),            # an empty sequence
+    ((900,) * 40, 8, 8, 128, 64),             # enough key blocks for the chip: one head group
+    ((2048,) * 20, 8, 8, 128, 64),            # ... with longer sequences
+    ((300,) * 8, 8, 8, 64, 32),               # equal lengths, eight sequences: a sequence per XCD, 2 head groups
     ((130,) * 16, 4, 2, 128, 64),             # ... GQA 2, three key blocks each, the last one ragged
-    ((1100,) * 24, 16, 16, 64, 64),           # ... one head group, selection launched separately
+    ((1100,) * 24, 16, 16, 64, 64),           # ... one head group
 ])
 def test_fused_step_equals_the_separate_calls(lib, lens, Hq, Hkv, d, w):
     wl = synth.shrunk(synth.workload("cfg2"), lens, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, w=w, hidden_dim=256)
@@ -73,7 +73,7 @@ def test_fused_step_equals_the_separate_calls(lib, lens, Hq, Hkv, d, w):
     ka = a["kept_idx"]
     assert np.array_equal(a["k_out"], x["k"][ka]) and np.array_equal(a["v_out"], x["v"][ka])
     assert np.array_equal(a["hidden_out"], x["hidden"][ka]) and np.array_equal(a["pos_out"], pos[ka])
-    # the selection in the tail is exact on the scores the fused pass itself produced
+    # the selection is exact on the scores the fused pass itself produced
     off = x["seq_offsets"]
     oo = a["out_offsets"]
     for s_i, S in enumerate(lens):

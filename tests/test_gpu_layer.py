@@ -82,9 +82,9 @@ def test_many_short_sequences(lib):
 
 
 @pytest.mark.parametrize("lens,Hq,Hkv,d,w", [
-    ((300,) * 8, 8, 8, 64, 32),                 # 2 head groups, selection in the score pass's tail
+    ((300,) * 8, 8, 8, 64, 32),                 # 2 head groups
     ((130,) * 16, 4, 2, 128, 64),               # GQA 2, the last key block ragged
-    ((1100,) * 8, 8, 4, 64, 64),                # beyond the tail's reach: the selection kernel
+    ((1100,) * 8, 8, 4, 64, 64),                # longer, 18 key blocks each
 ])
 def test_equal_lengths_in_multiples_of_eight(lib, lens, Hq, Hkv, d, w):
     """Batches of equal lengths and a multiple of eight sequences: the score pass keeps a sequence's key blocks on

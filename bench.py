@@ -153,6 +153,11 @@ class Step:
                                      self.keep_h, None, self.hidden, self.D * 2, None, self.out, self.scores, self.kept,
                                      self.out_off, self.k_out, self.v_out, self.hidden_out, None, self.ws, self.ws_bytes)
 
+    def static(self):
+        """the step through pyr_prefill_layer_static (K and V only, scratch memory inside the library: nothing allocated)"""
+        self.pyr.prefill_layer_static(self.q, self.k, self.v, self.off_d, self.off_h, self.shape, self.wl.w, 0.0, self.keep_d,
+                                      self.keep_h, self.out, self.scores, self.kept, self.out_off, self.k_out, self.v_out)
+
     def time_ms(self, fn, steps, warmup=2):
         torch = self.torch
         for _ in range(warmup):
@@ -377,7 +382,14 @@ def main():
             small[name] = {"kernel_ms_median_separate_calls": km, "select_over_attention": km["select"] / km["attention"],
                            "ms_per_step_separate_calls": s2.time_ms(s2.separate, 200, warmup=10),
                            "ms_per_step_fused_call": s2.time_ms(s2.fused, 200, warmup=10)}
-            del s2
+            # the launch-bound end of the range once more without the host in the loop: the step that allocates nothing
+            # (K and V only), eagerly and replayed from a HIP graph
+            small[name]["ms_per_step_static_call_kv_only"] = s2.time_ms(s2.static, 200, warmup=10)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                s2.static()
+            small[name]["ms_per_step_static_call_graph_replay"] = s2.time_ms(graph.replay, 200, warmup=10)
+            del graph, s2
         line["small_batch"] = small
 
     if args.cpu_seqs > 0:
